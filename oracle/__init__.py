@@ -1,0 +1,153 @@
+"""ctypes front end of the float64 CPU oracle (``rapid_oracle.c``).
+
+TEST INFRASTRUCTURE.  Only ``tests/``, the smoke check and the CPU-baseline leg
+of the benchmark may import this package; the GPU library never does, and this
+package never imports the GPU library.  It holds no arithmetic of its own:
+every number comes out of the C file, which is the thing to read against the
+paper.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rapid_oracle.c")
+_LIB = os.path.join(_HERE, "librapid_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (float64, OpenMP over independent units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Layout(ctypes.Structure):
+    _fields_ = [("batch_stride", ctypes.c_int64), ("token_stride", ctypes.c_int64),
+                ("head_stride", ctypes.c_int64), ("page_size", ctypes.c_int32),
+                ("page_stride", ctypes.c_int64), ("max_pages", ctypes.c_int32)]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_verify_attn.restype = ctypes.c_int
+        lib.oracle_accept.restype = ctypes.c_int
+        lib.oracle_distributions.restype = None
+        _lib = lib
+    return _lib
+
+
+def _ptr(a, ctype):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+@dataclass
+class KVLayout:
+    """Element strides of a KV cache (see ``oracle_kv_layout`` in the C file)."""
+    batch_stride: int
+    token_stride: int
+    head_stride: int
+    page_size: int = 0
+    page_stride: int = 0
+    max_pages: int = 0
+
+
+def verify_attn(q, k, v, ctx_lens, layout: KVLayout, *, Hkv, scale, gamma=None,
+                gammas=None, page_table=None, want_lse=False):
+    """q: uint16 (bf16 bits) [B,Qmax,Hq,d]; k, v: uint16 flat or shaped caches.
+
+    Returns out float64 [B,Qmax,Hq,d] (and lse float64 [B,Hq,Qmax])."""
+    lib = _load()
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    B, Qmax, Hq, d = q.shape
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    assert ctx_lens.shape == (B,)
+    if gammas is not None:
+        gammas = np.ascontiguousarray(gammas, dtype=np.int32)
+        g = 0
+    else:
+        g = Qmax - 1 if gamma is None else int(gamma)
+    if page_table is not None:
+        page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    lay = _Layout(layout.batch_stride, layout.token_stride, layout.head_stride,
+                  layout.page_size, layout.page_stride, layout.max_pages)
+    out = np.empty((B, Qmax, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq, Qmax), dtype=np.float64) if want_lse else None
+    rc = lib.oracle_verify_attn(
+        ctypes.c_int(B), ctypes.c_int(Qmax), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        ctypes.c_int(d), ctypes.c_double(scale),
+        _ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16), _ptr(v, ctypes.c_uint16),
+        ctypes.byref(lay), _ptr(page_table, ctypes.c_int32),
+        _ptr(ctx_lens, ctypes.c_int32), _ptr(gammas, ctypes.c_int32), ctypes.c_int(g),
+        _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_verify_attn: invalid argument (rc={rc})")
+    return (out, lse) if want_lse else out
+
+
+@dataclass
+class AcceptResult:
+    n_accepted: np.ndarray      # int32 [B]
+    out_tokens: np.ndarray      # int32 [B, gmax+1]
+    ratio: np.ndarray           # float64 [B, gmax]
+    accept_margin: np.ndarray   # float64 [B, gmax]
+    draw_margin: np.ndarray     # float64 [B]
+
+
+def accept(target_logits, draft_logits, draft_tokens, uniforms, *, eta, temperature=1.0,
+           tail_alpha=0.1, gammas=None) -> AcceptResult:
+    lib = _load()
+    zt = np.ascontiguousarray(target_logits, dtype=np.float32)
+    zd = np.ascontiguousarray(draft_logits, dtype=np.float32)
+    B, g1, V = zt.shape
+    gmax = g1 - 1
+    assert zd.shape == (B, gmax, V), (zd.shape, (B, gmax, V))
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gmax)
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    assert u.shape == (B, gmax + 1)
+    if gammas is not None:
+        gammas = np.ascontiguousarray(gammas, dtype=np.int32)
+    n_acc = np.empty((B,), dtype=np.int32)
+    out_tok = np.empty((B, gmax + 1), dtype=np.int32)
+    ratio = np.full((B, gmax), np.nan, dtype=np.float64)
+    amargin = np.full((B, gmax), np.inf, dtype=np.float64)
+    dmargin = np.zeros((B,), dtype=np.float64)
+    rc = lib.oracle_accept(
+        ctypes.c_int(B), ctypes.c_int(gmax), ctypes.c_int64(V),
+        _ptr(zt, ctypes.c_float), _ptr(zd, ctypes.c_float), _ptr(tok, ctypes.c_int32),
+        _ptr(gammas, ctypes.c_int32), ctypes.c_double(eta), ctypes.c_double(temperature),
+        ctypes.c_double(tail_alpha), _ptr(u, ctypes.c_float),
+        _ptr(n_acc, ctypes.c_int32), _ptr(out_tok, ctypes.c_int32),
+        _ptr(ratio, ctypes.c_double), _ptr(amargin, ctypes.c_double),
+        _ptr(dmargin, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_accept: invalid argument (rc={rc})")
+    return AcceptResult(n_acc, out_tok, ratio, amargin, dmargin)
+
+
+def distributions(z, zq, *, eta, temperature=1.0, tail_alpha=0.1):
+    """(p, q, p_hat) of one position, float64 [V] each."""
+    lib = _load()
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    zq = np.ascontiguousarray(zq, dtype=np.float64)
+    V = z.shape[0]
+    p = np.empty(V); q = np.empty(V); ph = np.empty(V)
+    lib.oracle_distributions(ctypes.c_int64(V), _ptr(z, ctypes.c_double),
+                             _ptr(zq, ctypes.c_double), ctypes.c_double(eta),
+                             ctypes.c_double(temperature), ctypes.c_double(tail_alpha),
+                             _ptr(p, ctypes.c_double), _ptr(q, ctypes.c_double),
+                             _ptr(ph, ctypes.c_double))
+    return p, q, ph

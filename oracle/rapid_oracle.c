@@ -1,0 +1,311 @@
+/*
+ * rapid_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, float64 CPU statement of what the RAPID verification step
+ * computes.  It exists so that the GPU library can be checked against
+ * something that can be compared with the paper by eye.  It shares no code,
+ * header, table or helper with the GPU library; only tests, the smoke check
+ * and the CPU-baseline leg of the benchmark may call it.
+ *
+ * Two functions:
+ *
+ *   oracle_verify_attn  -- the target model's attention for the gamma+1
+ *       verification positions against the whole KV cache ("validated by the
+ *       target model in a single forward pass", Sec. 2.1; Alg. 1 step
+ *       "z <- LogitsOf(p_phi(. | [C; x_<j]))").  The paper gives no formula
+ *       for attention itself: this is the textbook definition of causal,
+ *       grouped-query softmax attention written out per (sequence, query
+ *       position, query head) with a two-pass softmax.  No tiling, no online
+ *       rescaling, no splitting.
+ *
+ *   oracle_accept       -- Alg. 1, the body of the validation loop and the
+ *       residual draw, in the paper's order and notation:
+ *         p  = softmax(z/T), q = softmax(z_q/T)          (Alg. 1; Sec. 2.3)
+ *         zh = z + eta*T*(q - p)                         (Eq. "delta")
+ *         ph = softmax(zh/T)                             (Eq. "new_target")
+ *         ph_v <- p_v where ph_v < alpha * max_j ph_j    (tail rule, Sec. 2.4)
+ *         accept x' iff r <= min(1, ph(x')/q(x'))        (Alg. 1 accept test)
+ *         on first reject: x ~ norm(max(p-ph, p-q, 0))   (Alg. 1 residual)
+ *         all accepted:    x ~ p of the next position    (Sec. 2.1 background)
+ *       How a uniform number is turned into a token (inverse CDF in index
+ *       order) is an interface convention of this build, not the paper's.
+ *
+ * Pins: every function here is pinned by tests that do not call it to check
+ * itself (dense torch attention on tiny inputs, closed forms, the eta = 0
+ * reduction to textbook speculative sampling, chi-square against the
+ * analytically derived output law, finite differences of Proposition 1).
+ *
+ * All floating point is double.  bf16 inputs are widened exactly.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* bf16 (upper half of an IEEE binary32) -> double, exact.             */
+static double bf16_to_double(uint16_t bits)
+{
+    uint32_t w = ((uint32_t)bits) << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+/* Where token j of sequence b lives: element offset of (token, kv head, 0). */
+typedef struct {
+    int64_t batch_stride;   /* contiguous cache: elements between sequences        */
+    int64_t token_stride;   /* elements between consecutive tokens (in a page too) */
+    int64_t head_stride;    /* elements between kv heads of one token              */
+    int32_t page_size;      /* tokens per page, used only when page_table != NULL  */
+    int64_t page_stride;    /* elements between pages                              */
+    int32_t max_pages;      /* row length of page_table                            */
+} oracle_kv_layout;
+
+static int64_t kv_offset(const oracle_kv_layout* lay, const int32_t* page_table,
+                         int b, int64_t j, int hkv)
+{
+    if (page_table) {
+        int64_t page = page_table[(int64_t)b * lay->max_pages + j / lay->page_size];
+        int64_t slot = j % lay->page_size;
+        return page * lay->page_stride + slot * lay->token_stride + hkv * lay->head_stride;
+    }
+    return b * lay->batch_stride + j * lay->token_stride + hkv * lay->head_stride;
+}
+
+/*
+ * Causal GQA attention of the verification positions.
+ *
+ * q    : bf16 bits [B, Qmax, Hq, d]
+ * k, v : bf16 bits, addressed through `lay` (+ page_table when paged)
+ * ctx_lens[b] : number of valid tokens in the cache of sequence b, INCLUDING
+ *               the gamma_b+1 verification positions, which are its last ones
+ * gammas[b]   : number of draft tokens of sequence b (NULL -> gamma for all)
+ * out  : double [B, Qmax, Hq, d]; rows i > gamma_b are set to 0
+ * lse  : double [B, Hq, Qmax] natural-log sum-exp of the scaled scores, or NULL
+ *
+ * Query position i of sequence b sees keys 0 .. L-Q+i (L = ctx_lens[b],
+ * Q = gamma_b+1): the whole earlier context plus verification positions <= i.
+ * Query head h reads kv head h / (Hq/Hkv).
+ * Returns 0, or -1 on an invalid argument.
+ */
+int oracle_verify_attn(int B, int Qmax, int Hq, int Hkv, int d, double scale,
+                       const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                       const oracle_kv_layout* lay, const int32_t* page_table,
+                       const int32_t* ctx_lens, const int32_t* gammas, int gamma,
+                       double* out, double* lse)
+{
+    if (B < 0 || Qmax <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv) return -1;
+    const int G = Hq / Hkv;
+    for (int b = 0; b < B; ++b) {
+        int g = gammas ? gammas[b] : gamma;
+        if (g < 0 || g + 1 > Qmax || ctx_lens[b] < g + 1) return -1;
+    }
+    int64_t units = (int64_t)B * Qmax * Hq;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        int h = (int)(u % Hq);
+        int i = (int)((u / Hq) % Qmax);
+        int b = (int)(u / ((int64_t)Hq * Qmax));
+        int Q = (gammas ? gammas[b] : gamma) + 1;
+        int64_t L = ctx_lens[b];
+        double* o = out + u * d;
+        if (i >= Q) {
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            if (lse) lse[((int64_t)b * Hq + h) * Qmax + i] = 0.0;
+            continue;
+        }
+        int hkv = h / G;
+        int64_t nvis = L - Q + i + 1;           /* keys 0 .. L-Q+i */
+        double* s = (double*)malloc(sizeof(double) * (size_t)nvis);
+        double* qd = (double*)malloc(sizeof(double) * (size_t)d);
+        if (!s || !qd) { bad = 1; free(s); free(qd); continue; }
+        for (int c = 0; c < d; ++c)
+            qd[c] = bf16_to_double(q[u * d + c]);
+        /* pass 1: scores and their maximum */
+        double m = -INFINITY;
+        for (int64_t j = 0; j < nvis; ++j) {
+            const uint16_t* kr = k + kv_offset(lay, page_table, b, j, hkv);
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += qd[c] * bf16_to_double(kr[c]);
+            s[j] = scale * acc;
+            if (s[j] > m) m = s[j];
+        }
+        /* pass 2: weights, their sum, weighted sum of values */
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        double denom = 0.0;
+        for (int64_t j = 0; j < nvis; ++j) {
+            double w = exp(s[j] - m);
+            denom += w;
+            const uint16_t* vr = v + kv_offset(lay, page_table, b, j, hkv);
+            for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(vr[c]);
+        }
+        for (int c = 0; c < d; ++c) o[c] /= denom;
+        if (lse) lse[((int64_t)b * Hq + h) * Qmax + i] = m + log(denom);
+        free(s);
+        free(qd);
+    }
+    return bad ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* softmax(x / T) over n entries, max-subtracted.                      */
+static void softmax_T(const double* x, double T, int64_t n, double* out)
+{
+    double m = -INFINITY;
+    for (int64_t v = 0; v < n; ++v) if (x[v] / T > m) m = x[v] / T;
+    double sum = 0.0;
+    for (int64_t v = 0; v < n; ++v) { out[v] = exp(x[v] / T - m); sum += out[v]; }
+    for (int64_t v = 0; v < n; ++v) out[v] /= sum;
+}
+
+/*
+ * The three distributions of one verified position (Sec. 2.3-2.4).
+ *   p  = softmax(z/T)
+ *   q  = softmax(zq/T)
+ *   zh = z + eta*T*(q-p);  ph = softmax(zh/T)
+ *   tail rule: every entry of ph below tail_alpha * max(ph) is replaced by the
+ *   entry of p (mask taken from ph before any replacement; no renormalising).
+ * z, zq, p, q, ph: double[V].
+ */
+void oracle_distributions(int64_t V, const double* z, const double* zq,
+                          double eta, double T, double tail_alpha,
+                          double* p, double* q, double* ph)
+{
+    softmax_T(z, T, V, p);
+    softmax_T(zq, T, V, q);
+    double* zh = (double*)malloc(sizeof(double) * (size_t)V);
+    for (int64_t v = 0; v < V; ++v) zh[v] = z[v] + eta * T * (q[v] - p[v]);
+    softmax_T(zh, T, V, ph);
+    free(zh);
+    double mx = 0.0;
+    for (int64_t v = 0; v < V; ++v) if (ph[v] > mx) mx = ph[v];
+    double thr = tail_alpha * mx;
+    for (int64_t v = 0; v < V; ++v) if (ph[v] < thr) ph[v] = p[v];
+}
+
+/*
+ * Inverse-CDF draw from unnormalised non-negative weights w[0..V-1]:
+ * W = sum in index order, t = u*W, token = smallest v whose running sum
+ * (same order) exceeds t.  *margin = distance of t/W to the nearer edge of the
+ * chosen token's interval of the normalised CDF.  Returns -1 if W == 0.
+ */
+static int64_t draw_inverse_cdf(const double* w, int64_t V, double u, double* margin)
+{
+    double W = 0.0;
+    for (int64_t v = 0; v < V; ++v) W += w[v];
+    if (!(W > 0.0)) return -1;
+    double t = u * W, run = 0.0;
+    int64_t tok = -1;
+    double lo = 0.0;
+    for (int64_t v = 0; v < V; ++v) {
+        lo = run;
+        run += w[v];
+        if (run > t) { tok = v; break; }
+    }
+    if (tok < 0) {               /* u*W rounded up to W: last entry with weight */
+        for (int64_t v = V - 1; v >= 0; --v) if (w[v] > 0.0) { tok = v; break; }
+        if (margin) *margin = 0.0;
+        return tok;
+    }
+    if (margin) {
+        double a = (t - lo) / W, c = (run - t) / W;
+        *margin = a < c ? a : c;
+    }
+    return tok;
+}
+
+/*
+ * Accept / reject / resample for B sequences (Alg. 1, validation loop).
+ *
+ * target_logits : float [B, gmax+1, V]; row k is the target's logits for the
+ *                 position of draft k; row gamma_b is the position after the
+ *                 last draft (used only when all drafts are accepted)
+ * draft_logits  : float [B, gmax, V]
+ * draft_tokens  : int32 [B, gmax]
+ * gammas        : int32 [B] or NULL (-> gmax for all)
+ * uniforms      : float [B, gmax+1]; entry k < gamma_b drives accept test k,
+ *                 entry gmax drives the one draw
+ * n_accepted    : int32 [B]
+ * out_tokens    : int32 [B, gmax+1]: the accepted drafts, then the drawn
+ *                 token, then -1
+ * ratio         : double [B, gmax]  ph(x')/q(x') of every position (all rows
+ *                 are evaluated, also after the first reject), or NULL
+ * accept_margin : double [B, gmax]  |min(1, ratio) - r|, or NULL
+ * draw_margin   : double [B]        see draw_inverse_cdf, or NULL
+ * Returns 0, -1 on an invalid argument.
+ */
+int oracle_accept(int B, int gmax, int64_t V,
+                  const float* target_logits, const float* draft_logits,
+                  const int32_t* draft_tokens, const int32_t* gammas,
+                  double eta, double T, double tail_alpha,
+                  const float* uniforms,
+                  int32_t* n_accepted, int32_t* out_tokens,
+                  double* ratio, double* accept_margin, double* draw_margin)
+{
+    if (B < 0 || gmax < 0 || V <= 0 || !(T > 0.0) || eta < 0.0) return -1;
+    for (int b = 0; b < B; ++b) {
+        int g = gammas ? gammas[b] : gmax;
+        if (g < 0 || g > gmax) return -1;
+        for (int k = 0; k < g; ++k) {
+            int32_t x = draft_tokens[(int64_t)b * gmax + k];
+            if (x < 0 || x >= V) return -1;
+        }
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int g = gammas ? gammas[b] : gmax;
+        double* z  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* zq = (double*)malloc(sizeof(double) * (size_t)V);
+        double* p  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* q  = (double*)malloc(sizeof(double) * (size_t)V);
+        double* ph = (double*)malloc(sizeof(double) * (size_t)V);
+        double* w  = (double*)malloc(sizeof(double) * (size_t)V);
+        int32_t* toks = out_tokens + (int64_t)b * (gmax + 1);
+        for (int k = 0; k <= gmax; ++k) toks[k] = -1;
+
+        int n = g;                       /* number of accepted drafts            */
+        for (int k = 0; k < g; ++k) {
+            const float* zr  = target_logits + ((int64_t)b * (gmax + 1) + k) * V;
+            const float* zqr = draft_logits + ((int64_t)b * gmax + k) * V;
+            for (int64_t t = 0; t < V; ++t) { z[t] = zr[t]; zq[t] = zqr[t]; }
+            oracle_distributions(V, z, zq, eta, T, tail_alpha, p, q, ph);
+            int32_t x = draft_tokens[(int64_t)b * gmax + k];
+            double rho = q[x] > 0.0 ? ph[x] / q[x] : INFINITY;
+            double r = uniforms[(int64_t)b * (gmax + 1) + k];
+            double thr = rho < 1.0 ? rho : 1.0;
+            if (ratio) ratio[(int64_t)b * gmax + k] = rho;
+            if (accept_margin) accept_margin[(int64_t)b * gmax + k] = fabs(thr - r);
+            if (n == g && !(r <= thr)) {
+                n = k;                   /* first rejection; rows after it are   */
+                /* evaluated only to report their ratios                         */
+                for (int64_t t = 0; t < V; ++t) {
+                    double a = p[t] - ph[t], c = p[t] - q[t];
+                    double m = a > c ? a : c;
+                    w[t] = m > 0.0 ? m : 0.0;
+                }
+                double dm = 0.0;
+                int64_t tok = draw_inverse_cdf(w, V, uniforms[(int64_t)b * (gmax + 1) + gmax], &dm);
+                if (tok < 0)             /* empty residual: fall back to p       */
+                    tok = draw_inverse_cdf(p, V, uniforms[(int64_t)b * (gmax + 1) + gmax], &dm);
+                toks[k] = (int32_t)tok;
+                if (draw_margin) draw_margin[b] = dm;
+                if (!ratio && !accept_margin) break;
+            }
+        }
+        for (int k = 0; k < n; ++k) toks[k] = draft_tokens[(int64_t)b * gmax + k];
+        if (n == g) {                    /* every draft accepted: bonus from p   */
+            const float* zr = target_logits + ((int64_t)b * (gmax + 1) + g) * V;
+            for (int64_t t = 0; t < V; ++t) z[t] = zr[t];
+            softmax_T(z, T, V, p);
+            double dm = 0.0;
+            int64_t tok = draw_inverse_cdf(p, V, uniforms[(int64_t)b * (gmax + 1) + gmax], &dm);
+            toks[g] = (int32_t)tok;
+            if (draw_margin) draw_margin[b] = dm;
+        }
+        n_accepted[b] = n;
+        free(z); free(zq); free(p); free(q); free(ph); free(w);
+    }
+    return 0;
+}
