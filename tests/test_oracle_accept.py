@@ -150,6 +150,11 @@ def test_inverse_cdf_hand_cases():
     for u, want in edges:
         r = oracle.accept(z, zd, np.zeros((1, 0), np.int32), np.array([[u]], np.float32), eta=0.0)
         assert r.n_accepted[0] == 0 and r.out_tokens[0, 0] == want, (u, r.out_tokens)
+    # a zero-weight token is never drawn, not even by u = 0 (strict > on the running sum)
+    z0 = np.array([[[-np.inf, 0.0, 0.0]]], dtype=np.float32)
+    r = oracle.accept(z0, np.zeros((1, 0, 3), np.float32), np.zeros((1, 0), np.int32),
+                      np.array([[0.0]], np.float32), eta=0.0)
+    assert r.out_tokens[0, 0] == 1
 
 
 # ---------------------------------------------------------------- eta = 0: textbook SD
