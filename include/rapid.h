@@ -1,0 +1,159 @@
+/*
+ * rapid.h -- C ABI of the MI355X (gfx950) verification step of RAPID,
+ * retrieval-augmented speculative decoding.
+ *
+ * Two operations make up the step the target model performs on gamma drafted
+ * tokens (Alg. 1, validation loop):
+ *
+ *   rapid_verify_attn  attention of the gamma+1 verification positions against
+ *                      the whole long-context KV cache: the memory-bound part
+ *                      of "z <- LogitsOf(p_phi(. | [C; x_<j]))" done for all
+ *                      positions in one pass (Sec. 2.1, Alg. 1);
+ *   rapid_accept       p, q, the retrieval-augmented target p_hat
+ *                      (Eq. new_target / Eq. delta), the tail rule (Sec. 2.4),
+ *                      the accept test and the residual / bonus draw (Alg. 1).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller
+ *     owns all buffers; the library allocates no device memory, keeps no
+ *     pointer after a call returns, and only enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).  Calls are
+ *     asynchronous: synchronise the stream before reading results.
+ *   - Shapes and strides are host values.  bf16 tensors are raw 16-bit words.
+ *   - Every function returns 0 or a negative rapid_status; nothing aborts or
+ *     prints.  After RAPID_EHIP, rapid_last_hip_error() gives the HIP code.
+ *   - Two calls that share a workspace must not overlap in time.
+ */
+#ifndef RAPID_H
+#define RAPID_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rapid_status {
+    RAPID_OK = 0,
+    RAPID_EINVAL = -1,        /* NULL pointer, non-positive size, gamma/ctx out of range, eta < 0, T <= 0 */
+    RAPID_EALIGN = -2,        /* q/k/v/out not 16-byte aligned, or a stride not a multiple of 8 elements  */
+    RAPID_EUNSUPPORTED = -3,  /* head_dim not 64/128, (gamma+1)*group > 80, page size not a power of two >= 16 */
+    RAPID_EWORKSPACE = -4,    /* workspace NULL, misaligned or smaller than the *_workspace_bytes() answer */
+    RAPID_EHIP = -5           /* a HIP runtime call failed */
+} rapid_status;
+
+typedef struct rapid_ctx rapid_ctx;   /* opaque; caches device properties, owns no device memory */
+
+/* Create a context for HIP device `device`.  `*out` is host memory. */
+int rapid_create(rapid_ctx** out, int device);
+void rapid_destroy(rapid_ctx* ctx);
+const char* rapid_strerror(int status);
+int rapid_last_hip_error(const rapid_ctx* ctx);
+
+/*
+ * Shape of one rapid_verify_attn call (host struct).
+ *
+ * KV cache addressing, in ELEMENTS (bf16 words); element (b, token j, kv head h, c):
+ *   contiguous (page_size == 0):  b*kv_batch_stride + j*kv_token_stride + h*kv_head_stride + c
+ *   paged (page_size > 0):        page_table[b][j / page_size]*kv_page_stride
+ *                                 + (j % page_size)*kv_token_stride + h*kv_head_stride + c
+ * The head_dim elements of one (token, head) are contiguous.  K and V use the
+ * same strides.  The natural layouts are [B, max_ctx, Hkv, d] and
+ * [n_pages, page_size, Hkv, d].
+ */
+typedef struct rapid_attn_shape {
+    int32_t batch;            /* B >= 1                                                        */
+    int32_t q_max;            /* Qmax = max_b gamma_b + 1: query rows per sequence in q / out  */
+    int32_t n_q_heads;        /* Hq                                                            */
+    int32_t n_kv_heads;       /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv)      */
+    int32_t head_dim;         /* d: 64 or 128                                                  */
+    int32_t max_ctx;          /* upper bound of ctx_lens[b]; sizes the grid and the workspace  */
+    int32_t gamma;            /* drafts per sequence when gammas == NULL (0 <= gamma < q_max)  */
+    float   softmax_scale;    /* > 0; scores are softmax_scale * <q, k>                        */
+    int64_t kv_batch_stride;
+    int64_t kv_token_stride;
+    int64_t kv_head_stride;
+    int64_t kv_page_stride;
+    int32_t page_size;        /* 0 = contiguous cache, else a power of two >= 16               */
+    int32_t max_pages;        /* row length of page_table                                      */
+    int32_t chunk_tokens;     /* tokens per KV split; 0 = let the library choose               */
+} rapid_attn_shape;
+
+/* Tokens per KV split the library will use for `shape` (multiple of 128), and
+ * through it the number of splits per (sequence, kv head): ceil(max_ctx / chunk). */
+int rapid_verify_attn_chunk(const rapid_ctx* ctx, const rapid_attn_shape* shape);
+
+/* Bytes of device workspace rapid_verify_attn needs for `shape` (0 on a bad shape). */
+size_t rapid_verify_attn_workspace_bytes(const rapid_ctx* ctx, const rapid_attn_shape* shape);
+
+/*
+ * Causal grouped-query attention of the verification positions (Sec. 2.1:
+ * gamma candidates "validated by the target model in a single forward pass";
+ * Alg. 1: target logits conditioned on [C; x_<j] for every drafted position j).
+ *
+ * For sequence b let L = ctx_lens[b], Q = gamma_b + 1.  The cache already holds
+ * K/V of the Q verification positions as its LAST Q valid tokens (L counts
+ * them).  Query row i (0 <= i < Q) of head h attends keys 0 .. L-Q+i:
+ *     out[b,i,h,:] = softmax_j(softmax_scale * <q[b,i,h,:], k[b,j,h/G,:]>) . v[b,j,h/G,:]
+ * computed with fp32 accumulation from bf16 inputs, result rounded to bf16.
+ * Rows i >= Q are written as zeros.  Rotary embedding etc. are the caller's.
+ *
+ *   q          bf16 [B, Qmax, Hq, d], contiguous
+ *   k_cache    bf16, see rapid_attn_shape
+ *   v_cache    bf16, same addressing as k_cache
+ *   ctx_lens   int32 [B], gamma_b+1 <= ctx_lens[b] <= max_ctx (unchecked: device data)
+ *   gammas     int32 [B] or NULL (-> shape->gamma for all), 0 <= gamma_b < Qmax
+ *   page_table int32 [B, max_pages] when page_size > 0, else NULL
+ *   out        bf16 [B, Qmax, Hq, d]
+ *   lse_out    fp32 [B, Hq, Qmax] natural-log sum-exp of the scaled scores, or NULL
+ *   workspace  >= rapid_verify_attn_workspace_bytes(), 256-byte aligned
+ */
+int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
+                      const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* ctx_lens, const int32_t* gammas,
+                      const int32_t* page_table,
+                      void* out, float* lse_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device workspace rapid_accept needs (0 on bad sizes). */
+size_t rapid_accept_workspace_bytes(const rapid_ctx* ctx, int batch, int gamma_max, int vocab);
+
+/*
+ * Accept / reject / resample for `batch` sequences (Alg. 1, validation loop).
+ * For sequence b with g = gamma_b drafts, rows k = 0..g-1, temperature T:
+ *     p_k  = softmax(z_k / T),  q_k = softmax(zq_k / T)
+ *     ph_k = softmax(z_k / T + eta (q_k - p_k))                 (Eq. new_target)
+ *     ph_k(v) <- p_k(v) where ph_k(v) < tail_alpha * max ph_k   (tail rule; mask from the
+ *                                                                unreplaced ph_k, no renormalising)
+ *     draft k accepted iff uniforms[b,k] <= min(1, ph_k(x_k) / q_k(x_k))
+ *     n = index of the first rejected draft, or g
+ *     n < g : token ~ norm(max(p_n - ph_n, p_n - q_n, 0))       (Alg. 1 residual)
+ *     n = g : token ~ p_g  (target row g, the position after the last draft)
+ * The draw is the inverse CDF in vocabulary order driven by uniforms[b, gamma_max]:
+ * the smallest v whose running sum of weights exceeds u * (total weight).
+ *
+ *   target_logits fp32 [B, gamma_max+1, V]
+ *   draft_logits  fp32 [B, gamma_max,   V]
+ *   draft_tokens  int32 [B, gamma_max]; an id outside [0, V) rejects that position
+ *   gammas        int32 [B] or NULL (-> gamma_max), 0 <= gamma_b <= gamma_max
+ *   eta >= 0, temperature > 0, tail_alpha >= 0 (0 disables the tail rule; the paper uses 0.1)
+ *   uniforms      fp32 [B, gamma_max+1] in [0, 1)
+ *   n_accepted    int32 [B]
+ *   out_tokens    int32 [B, gamma_max+1]: accepted drafts, the drawn token, then -1
+ *   accept_ratio  fp32 [B, gamma_max] ph_k(x_k)/q_k(x_k) of every row k < gamma_b
+ *                 (also after the first reject), or NULL
+ *   workspace     >= rapid_accept_workspace_bytes(), 256-byte aligned
+ */
+int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
+                 const float* target_logits, const float* draft_logits,
+                 const int32_t* draft_tokens, const int32_t* gammas,
+                 float eta, float temperature, float tail_alpha,
+                 const float* uniforms,
+                 int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPID_H */

@@ -1,0 +1,224 @@
+"""ctypes binding of librapid.so: argument marshalling only.
+
+Every step of the verification path runs in the library's gfx950 kernels; torch
+supplies device memory and the stream.  There is no CPU fallback: if the library
+has not been built, importing works but the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librapid.so")
+
+RAPID_OK = 0
+EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
+           "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
+           "rapid_accept_workspace_bytes", "rapid_accept"]
+
+
+class RapidError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"librapid: {message} (status {status})")
+        self.status = status
+
+
+class AttnShape(ctypes.Structure):
+    """Mirror of ``rapid_attn_shape`` in include/rapid.h."""
+    _fields_ = [("batch", ctypes.c_int32), ("q_max", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("max_ctx", ctypes.c_int32),
+                ("gamma", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("kv_batch_stride", ctypes.c_int64), ("kv_token_stride", ctypes.c_int64),
+                ("kv_head_stride", ctypes.c_int64), ("kv_page_stride", ctypes.c_int64),
+                ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
+                ("chunk_tokens", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load librapid.so and declare the C signatures.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RapidError(-100, f"{LIB_PATH} not found: build it with "
+                               "`python -m paper_2502_20330_amd.build` (there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    lib.rapid_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
+    lib.rapid_create.restype = ctypes.c_int
+    lib.rapid_destroy.argtypes = [ctypes.c_void_p]
+    lib.rapid_destroy.restype = None
+    lib.rapid_strerror.argtypes = [ctypes.c_int]
+    lib.rapid_strerror.restype = ctypes.c_char_p
+    lib.rapid_last_hip_error.argtypes = [ctypes.c_void_p]
+    lib.rapid_last_hip_error.restype = ctypes.c_int
+    lib.rapid_verify_attn_chunk.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape)]
+    lib.rapid_verify_attn_chunk.restype = ctypes.c_int
+    lib.rapid_verify_attn_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape)]
+    lib.rapid_verify_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.rapid_verify_attn.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape), vp, vp, vp, i32p, i32p, i32p,
+                                      vp, f32p, vp, ctypes.c_size_t, vp]
+    lib.rapid_verify_attn.restype = ctypes.c_int
+    lib.rapid_accept_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.rapid_accept_workspace_bytes.restype = ctypes.c_size_t
+    lib.rapid_accept.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, f32p, f32p, i32p, i32p,
+                                 ctypes.c_float, ctypes.c_float, ctypes.c_float, f32p, i32p, i32p, f32p,
+                                 vp, ctypes.c_size_t, vp]
+    lib.rapid_accept.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(lib, status: int, ctx=None):
+    if status != RAPID_OK:
+        msg = lib.rapid_strerror(status).decode()
+        if ctx is not None and status == -5:
+            msg += f" (hip error {lib.rapid_last_hip_error(ctx)})"
+        raise RapidError(status, msg)
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+class Rapid:
+    """One library context on one GPU plus a grow-only workspace tensor."""
+
+    def __init__(self, device: int = 0):
+        if not torch.cuda.is_available():
+            raise RapidError(-101, "no GPU visible: the verification path has no CPU implementation")
+        self.lib = load_library()
+        self.device = torch.device("cuda", device)
+        self._ctx = ctypes.c_void_p()
+        torch.cuda.set_device(self.device)
+        _check(self.lib, self.lib.rapid_create(ctypes.byref(self._ctx), device))
+        self._ws: Optional[torch.Tensor] = None
+
+    def close(self):
+        if self._ctx:
+            self.lib.rapid_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _workspace(self, nbytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    # ------------------------------------------------------------------ attention
+    def attn_shape(self, q, k_cache, ctx_max: int, *, gamma: Optional[int] = None, page_table=None,
+                   softmax_scale: Optional[float] = None, chunk_tokens: int = 0) -> AttnShape:
+        B, Qmax, Hq, d = q.shape
+        s = AttnShape()
+        s.batch, s.q_max, s.n_q_heads, s.head_dim = B, Qmax, Hq, d
+        s.n_kv_heads = k_cache.shape[2]
+        s.max_ctx = int(ctx_max)
+        s.gamma = Qmax - 1 if gamma is None else int(gamma)
+        s.softmax_scale = float(softmax_scale) if softmax_scale is not None else d ** -0.5
+        st = k_cache.stride()
+        if k_cache.stride(3) != 1:
+            raise RapidError(-1, "head_dim must be the contiguous dimension of the KV cache")
+        if page_table is None:
+            s.kv_batch_stride, s.kv_token_stride, s.kv_head_stride = st[0], st[1], st[2]
+            s.kv_page_stride, s.page_size, s.max_pages = 0, 0, 0
+        else:
+            s.kv_page_stride, s.kv_token_stride, s.kv_head_stride = st[0], st[1], st[2]
+            s.kv_batch_stride = 0
+            s.page_size, s.max_pages = k_cache.shape[1], page_table.shape[1]
+        s.chunk_tokens = int(chunk_tokens)
+        return s
+
+    def verify_attn_chunk(self, shape: AttnShape) -> int:
+        c = self.lib.rapid_verify_attn_chunk(self._ctx, ctypes.byref(shape))
+        if c < 0:
+            _check(self.lib, c)
+        return c
+
+    def rapid_verify_attn(self, q, k_cache, v_cache, ctx_lens, gamma: Optional[int] = None, *, gammas=None,
+                          page_table=None, max_ctx: Optional[int] = None, softmax_scale: Optional[float] = None,
+                          chunk_tokens: int = 0, out=None, lse_out=None, shape: Optional[AttnShape] = None):
+        """q bf16 [B,Qmax,Hq,d]; k_cache/v_cache bf16 [B,Lmax,Hkv,d] (any batch/token/head strides)
+        or paged [n_pages,page,Hkv,d] with page_table int32 [B,max_pages]; ctx_lens int32 [B]
+        (device).  ``max_ctx`` is a host upper bound of ctx_lens (default: the cache capacity).
+        Returns out bf16 [B,Qmax,Hq,d]; fills lse_out fp32 [B,Hq,Qmax] if given."""
+        assert q.dtype == torch.bfloat16 and k_cache.dtype == torch.bfloat16 and v_cache.dtype == torch.bfloat16
+        assert q.is_contiguous() and ctx_lens.dtype == torch.int32
+        assert k_cache.stride() == v_cache.stride() and k_cache.shape == v_cache.shape
+        if shape is None:
+            if max_ctx is None:
+                max_ctx = k_cache.shape[1] if page_table is None else page_table.shape[1] * k_cache.shape[1]
+            shape = self.attn_shape(q, k_cache, max_ctx, gamma=gamma, page_table=page_table,
+                                    softmax_scale=softmax_scale, chunk_tokens=chunk_tokens)
+        if out is None:
+            out = torch.empty_like(q)
+        need = self.lib.rapid_verify_attn_workspace_bytes(self._ctx, ctypes.byref(shape))
+        ws = self._workspace(need)
+        rc = self.lib.rapid_verify_attn(self._ctx, ctypes.byref(shape), _dptr(q), _dptr(k_cache), _dptr(v_cache),
+                                        _dptr(ctx_lens), _dptr(gammas), _dptr(page_table), _dptr(out),
+                                        _dptr(lse_out), _dptr(ws), ws.numel(), _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return out
+
+    # ------------------------------------------------------------------ accept
+    def rapid_accept(self, target_logits, draft_logits, draft_tokens, eta: float, uniforms, *, gammas=None,
+                     temperature: float = 1.0, tail_alpha: float = 0.1, want_ratio: bool = True, outs=None):
+        """target_logits fp32 [B,g+1,V], draft_logits fp32 [B,g,V], draft_tokens int32 [B,g],
+        uniforms fp32 [B,g+1].  Returns (n_accepted int32 [B], out_tokens int32 [B,g+1], ratio fp32 [B,g] or None)."""
+        B, g1, V = target_logits.shape
+        g = g1 - 1
+        assert target_logits.dtype == torch.float32 and target_logits.is_contiguous()
+        assert draft_logits.dtype == torch.float32 and draft_logits.is_contiguous() and draft_logits.shape == (B, g, V)
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, g) and draft_tokens.is_contiguous()
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (B, g + 1) and uniforms.is_contiguous()
+        if outs is None:
+            n_acc = torch.empty(B, dtype=torch.int32, device=self.device)
+            toks = torch.empty(B, g + 1, dtype=torch.int32, device=self.device)
+            ratio = torch.zeros(B, max(g, 1), dtype=torch.float32, device=self.device)[:, :g] if want_ratio else None
+            if ratio is not None:
+                ratio = ratio.contiguous()
+        else:
+            n_acc, toks, ratio = outs
+        need = self.lib.rapid_accept_workspace_bytes(self._ctx, B, g, V)
+        ws = self._workspace(need)
+        rc = self.lib.rapid_accept(self._ctx, B, g, V, _dptr(target_logits), _dptr(draft_logits),
+                                   _dptr(draft_tokens), _dptr(gammas), float(eta), float(temperature),
+                                   float(tail_alpha), _dptr(uniforms), _dptr(n_acc), _dptr(toks), _dptr(ratio),
+                                   _dptr(ws), ws.numel(), _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return n_acc, toks, ratio
+
+
+_default: dict = {}
+
+
+def _get(device: int = 0) -> Rapid:
+    if device not in _default:
+        _default[device] = Rapid(device)
+    return _default[device]
+
+
+def rapid_verify_attn(q, k_cache, v_cache, ctx_lens, gamma=None, **kw):
+    """Module-level form of :meth:`Rapid.rapid_verify_attn` on the tensors' device."""
+    return _get(q.device.index or 0).rapid_verify_attn(q, k_cache, v_cache, ctx_lens, gamma, **kw)
+
+
+def rapid_accept(target_logits, draft_logits, draft_tokens, eta, uniforms, **kw):
+    """Module-level form of :meth:`Rapid.rapid_accept` on the tensors' device."""
+    return _get(target_logits.device.index or 0).rapid_accept(target_logits, draft_logits, draft_tokens, eta,
+                                                              uniforms, **kw)

@@ -1,0 +1,415 @@
+// Acceptance pass of RAPID's validation loop (Alg. 1) for gfx950 (MI355X).
+//
+// Per sequence b and drafted position k the paper defines
+//   p = softmax(z/T), q = softmax(z_q/T)                       (Alg. 1)
+//   p_hat = softmax(z/T + eta (q - p))                         (Eq. new_target)
+//   p_hat(v) <- p(v) where p_hat(v) < alpha * max p_hat        (tail rule, Sec. 2.4)
+//   accept x' iff r <= min(1, p_hat(x')/q(x'))                 (Alg. 1)
+//   first reject: x ~ norm(max(p - p_hat, p - q, 0)); none: x ~ p of the next row.
+//
+// The accept test at a position needs p, q, p_hat only at the one drafted token,
+// given three log-normalisers per row; only the row where the draw happens needs
+// an elementwise pass.  So the work is organised as reductions over the
+// vocabulary, chunked over many workgroups so the logits stream at HBM rate:
+//
+//   K1 row_stats      : per chunk (max z, sum exp((z - max)/T)) of every target and draft row
+//   K2 shifted_stats  : per chunk (max, sum exp) of d = (z - zmax)/T + eta (q - p)
+//   K3 decide         : combine chunks -> log-normalisers (double); accept tests in
+//                       double at the drafted tokens; first reject n; prefix of out_tokens
+//   K4 residual_sums  : per chunk sum of the draw weights of row n (double)
+//   K5 draw           : locate the chunk and the token where the running sum passes u*W
+//
+// Sums over the vocabulary run in fp32 per thread and are combined in fp64;
+// everything that decides an integer (accept test, draw) is evaluated in fp64.
+// Statistics are kept relative to the raw row maximum so that dividing by T
+// costs no absolute precision.
+#include "rapid_internal.h"
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kChunk = 1024;            // vocabulary entries per workgroup (4 per thread)
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Block-wide reductions over kThreads threads; `sh` has >= 4 slots; the result
+// is returned to every thread.
+#define RAPID_BLOCK_REDUCE(NAME, T, WAVE_OP, COMBINE)                      \
+    __device__ __forceinline__ T NAME(T v, T* sh)                          \
+    {                                                                      \
+        v = WAVE_OP(v);                                                    \
+        __syncthreads();                                                   \
+        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;             \
+        __syncthreads();                                                   \
+        T r = sh[0];                                                       \
+        for (int w = 1; w < kThreads / 64; ++w) r = COMBINE(r, sh[w]);     \
+        return r;                                                          \
+    }
+#define RAPID_ADD(a, b) ((a) + (b))
+RAPID_BLOCK_REDUCE(block_max, float, wave_max, fmaxf)
+RAPID_BLOCK_REDUCE(block_sum, float, wave_sum, RAPID_ADD)
+RAPID_BLOCK_REDUCE(block_max, double, wave_max, fmax)
+RAPID_BLOCK_REDUCE(block_sum, double, wave_sum, RAPID_ADD)
+
+// Four consecutive logits of a row starting at index i (i % 4 == 0); entries at or
+// past V come back as -inf.  `vec` says the row base is 16-byte aligned.
+__device__ __forceinline__ floatx4 load4(const float* row, int i, int V, bool vec)
+{
+    floatx4 r = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (vec && i + 3 < V) return *reinterpret_cast<const floatx4*>(row + i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (i + j < V) r[j] = row[i + j];
+    return r;
+}
+
+struct Ws {
+    float2* st_t;     // [B][gmax+1][nch]  (raw max, sum exp((z-max)/T))
+    float2* st_d;     // [B][gmax][nch]
+    float2* st_h;     // [B][gmax][nch]    (max d, sum exp(d - max d)), d relative to the target row max / T
+    double* rows;     // [B][gmax+1][8]: zmax_t, lse_p, zmax_d, lse_q, lse_h, 1/S_h (= max p_hat), -, -
+    double* wsum;     // [B][nch][2]: sum of residual weights, sum of p (fallback)
+    int nch;
+};
+
+__host__ __device__ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+__host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
+{
+    Ws w;
+    w.nch = (V + kChunk - 1) / kChunk;
+    char* p = static_cast<char*>(base);
+    w.st_t = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax + 1) * w.nch * sizeof(float2));
+    w.st_d = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
+    w.st_h = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
+    w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 8 * sizeof(double));
+    w.wsum = reinterpret_cast<double*>(p); p += align256((size_t)B * w.nch * 2 * sizeof(double));
+    return w;
+}
+
+// ---------------------------------------------------------------- K1
+__global__ void __launch_bounds__(kThreads) accept_row_stats(AcceptLaunch a, Ws ws)
+{
+    __shared__ float sh[8];
+    const int ch = blockIdx.x, y = blockIdx.y, b = blockIdx.z;
+    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const bool is_t = y <= a.gmax;
+    const int k = is_t ? y : y - (a.gmax + 1);
+    if (is_t ? (k > g) : (k >= g)) return;
+    const float* row = is_t ? a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V
+                            : a.zd + ((int64_t)b * a.gmax + k) * a.V;
+    const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15) == 0);
+    floatx4 x = load4(row, ch * kChunk + threadIdx.x * 4, a.V, vec);
+    float m = block_max(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), sh);
+    float s = 0.f;
+    if (m > -INFINITY) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s += fexp((x[j] - m) * a.inv_T);
+    }
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) {
+        float2* dst = is_t ? ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch
+                           : ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch;
+        dst[ch] = make_float2(m, s);
+    }
+}
+
+// Combine per-chunk (max, sum) pairs of a row: returns the row max and
+// S = sum_i s_i exp((m_i - max) * inv_T) (inv_T = 1 when the maxima are already scaled).
+__device__ __forceinline__ void combine_row(const float2* st, int nch, double inv_T, double* shd,
+                                            double& M, double& S)
+{
+    double m = -INFINITY;
+    for (int i = threadIdx.x; i < nch; i += kThreads) m = fmax(m, (double)st[i].x);
+    M = block_max(m, shd);
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nch; i += kThreads) {
+        float2 v = st[i];
+        if (v.y > 0.f) s += (double)v.y * exp(((double)v.x - M) * inv_T);
+    }
+    S = block_sum(s, shd);
+}
+
+// ---------------------------------------------------------------- K2
+__global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a, Ws ws)
+{
+    __shared__ float sh[8];
+    __shared__ double shd[8];
+    const int ch = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
+    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    if (k >= g) return;
+    double Mt, St, Md, Sd;
+    combine_row(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Mt, St);
+    combine_row(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Md, Sd);
+    const float zmax_t = (float)Mt, zmax_d = (float)Md;       // exact: they are float values
+    const float lnS_t = (float)log(St), lnS_d = (float)log(Sd);
+    const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
+    const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
+    const bool vec = ((reinterpret_cast<uintptr_t>(zt) & 15) == 0) && ((reinterpret_cast<uintptr_t>(zd) & 15) == 0);
+    const int i0 = ch * kChunk + threadIdx.x * 4;
+    floatx4 x = load4(zt, i0, a.V, vec), y = load4(zd, i0, a.V, vec);
+    float d[4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float at = (x[j] - zmax_t) * a.inv_T;              // z/T relative to the row max
+        float ad = (y[j] - zmax_d) * a.inv_T;
+        float p = fexp(at - lnS_t), q = fexp(ad - lnS_d);
+        d[j] = (i0 + j < a.V) ? fmaf(a.eta, q - p, at) : -INFINITY;
+        m = fmaxf(m, d[j]);
+    }
+    m = block_max(m, sh);
+    float s = 0.f;
+    if (m > -INFINITY) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s += fexp(d[j] - m);
+    }
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) ws.st_h[((int64_t)b * a.gmax + k) * ws.nch + ch] = make_float2(m, s);
+}
+
+// ---------------------------------------------------------------- K3
+__global__ void __launch_bounds__(kThreads) accept_decide(AcceptLaunch a, Ws ws)
+{
+    __shared__ double shd[8];
+    const int b = blockIdx.x;
+    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    double* rows = ws.rows + (int64_t)b * (a.gmax + 1) * 8;
+    for (int k = 0; k <= g; ++k) {
+        double Mt, St;
+        combine_row(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Mt, St);
+        double Md = 0, Sd = 1, Mh = 0, Sh = 1;
+        if (k < g) {
+            combine_row(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Md, Sd);
+            combine_row(ws.st_h + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, 1.0, shd, Mh, Sh);
+        }
+        if (threadIdx.x == 0) {
+            double* r = rows + k * 8;
+            r[0] = Mt;                                   // raw max of the target row
+            r[1] = log(St);                              // lse_p = r[0]/T + r[1]
+            r[2] = Md;
+            r[3] = log(Sd);
+            r[4] = Mh + log(Sh);                         // lse_h = r[0]/T + r[4]
+            r[5] = 1.0 / Sh;                             // max p_hat
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    __threadfence_block();
+    const double invT = (double)a.inv_T_exact;
+    int n = g;
+    int32_t* toks = a.out_tokens + (int64_t)b * (a.gmax + 1);
+    for (int k = 0; k < g; ++k) {
+        const double* r = rows + k * 8;
+        int x = a.tokens[(int64_t)b * a.gmax + k];
+        double rho = 0.0;
+        bool ok = false;
+        if (x >= 0 && x < a.V) {
+            double at = ((double)a.zt[((int64_t)b * (a.gmax + 1) + k) * a.V + x] - r[0]) * invT;
+            double ad = ((double)a.zd[((int64_t)b * a.gmax + k) * a.V + x] - r[2]) * invT;
+            double p = exp(at - r[1]), q = exp(ad - r[3]);
+            double ph = exp(at + (double)a.eta * (q - p) - r[4]);
+            if (ph < (double)a.tail_alpha * r[5]) ph = p;
+            rho = q > 0.0 ? ph / q : INFINITY;
+            double u = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + k];
+            ok = u <= fmin(1.0, rho);
+        }
+        if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
+        if (!ok && n == g) n = k;
+    }
+    for (int k = 0; k <= a.gmax; ++k) toks[k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
+    a.n_accepted[b] = n;
+}
+
+// Draw weight of vocabulary entry v of row n (fp64): the residual
+// max(p - p_hat', p - q, 0) when n < g, p itself for the bonus row n = g.
+struct RowCtx {
+    const float* zt;
+    const float* zd;
+    double zmax_t, lnS_t, zmax_d, lnS_d, lse_h_rel, tail_thr, eta, invT;
+    bool bonus;
+};
+__device__ __forceinline__ RowCtx make_row_ctx(const AcceptLaunch& a, const Ws& ws, int b, int n, int g)
+{
+    RowCtx c;
+    const double* r = ws.rows + ((int64_t)b * (a.gmax + 1) + n) * 8;
+    c.zt = a.zt + ((int64_t)b * (a.gmax + 1) + n) * a.V;
+    c.zd = n < g ? a.zd + ((int64_t)b * a.gmax + n) * a.V : nullptr;
+    c.zmax_t = r[0]; c.lnS_t = r[1]; c.zmax_d = r[2]; c.lnS_d = r[3]; c.lse_h_rel = r[4];
+    c.tail_thr = (double)a.tail_alpha * r[5];
+    c.eta = (double)a.eta;
+    c.invT = (double)a.inv_T_exact;
+    c.bonus = n >= g;
+    return c;
+}
+__device__ __forceinline__ void weights(const RowCtx& c, int v, double& w, double& p)
+{
+    double at = ((double)c.zt[v] - c.zmax_t) * c.invT;
+    p = exp(at - c.lnS_t);
+    if (c.bonus) { w = p; return; }
+    double ad = ((double)c.zd[v] - c.zmax_d) * c.invT;
+    double q = exp(ad - c.lnS_d);
+    double ph = exp(at + c.eta * (q - p) - c.lse_h_rel);
+    if (ph < c.tail_thr) ph = p;
+    w = fmax(fmax(p - ph, p - q), 0.0);
+}
+
+// ---------------------------------------------------------------- K4
+__global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a, Ws ws)
+{
+    __shared__ double shd[8];
+    const int ch = blockIdx.x, b = blockIdx.y;
+    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int n = a.n_accepted[b];
+    RowCtx c = make_row_ctx(a, ws, b, n, g);
+    double sw = 0.0, sp = 0.0;
+    const int i0 = ch * kChunk + threadIdx.x * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (i0 + j < a.V) {
+            double w, p;
+            weights(c, i0 + j, w, p);
+            sw += w;
+            sp += p;
+        }
+    }
+    sw = block_sum(sw, shd);
+    sp = block_sum(sp, shd);
+    if (threadIdx.x == 0) {
+        ws.wsum[((int64_t)b * ws.nch + ch) * 2 + 0] = sw;
+        ws.wsum[((int64_t)b * ws.nch + ch) * 2 + 1] = sp;
+    }
+}
+
+// ---------------------------------------------------------------- K5
+__global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
+{
+    __shared__ double shd[8];
+    __shared__ double scan[kThreads];
+    __shared__ int pick_chunk, pick_lo, pick_hi;
+    __shared__ double chunk_base;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int n = a.n_accepted[b];
+    RowCtx c = make_row_ctx(a, ws, b, n, g);
+    const double* cs = ws.wsum + (int64_t)b * ws.nch * 2;
+
+    double tw = 0.0;
+    for (int i = tid; i < ws.nch; i += kThreads) tw += cs[i * 2];
+    const double Wres = block_sum(tw, shd);
+    const int col = Wres > 0.0 ? 0 : 1;          // empty residual: draw from p instead
+    double W = Wres;
+    if (col == 1) {
+        double tp = 0.0;
+        for (int i = tid; i < ws.nch; i += kThreads) tp += cs[i * 2 + 1];
+        W = block_sum(tp, shd);
+    }
+    const double t = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + a.gmax] * W;
+
+    // chunk whose inclusive running sum first exceeds t (chunks in vocabulary order)
+    if (tid == 0) {
+        double run = 0.0;
+        int pc = -1, last_pos = 0;
+        double base = 0.0;
+        for (int i = 0; i < ws.nch; ++i) {
+            double v = cs[i * 2 + col];
+            if (v > 0.0) last_pos = i;
+            if (pc < 0 && run + v > t) { pc = i; base = run; }
+            run += v;
+        }
+        if (pc < 0) {                             // t rounded up to W
+            pc = last_pos;
+            base = run - cs[last_pos * 2 + col];
+        }
+        pick_chunk = pc;
+        chunk_base = base;
+        pick_lo = 0x7fffffff;
+        pick_hi = -1;
+    }
+    __syncthreads();
+    const int i0 = pick_chunk * kChunk + tid * 4;
+    double w[4], local = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        w[j] = 0.0;
+        if (i0 + j < a.V) {
+            double ww, pp;
+            weights(c, i0 + j, ww, pp);
+            w[j] = col == 0 ? ww : pp;
+        }
+        local += w[j];
+    }
+    scan[tid] = local;
+    __syncthreads();
+    // exclusive prefix of the per-thread sums (Hillis-Steele over 256 entries)
+    for (int o = 1; o < kThreads; o <<= 1) {
+        double add = tid >= o ? scan[tid - o] : 0.0;
+        __syncthreads();
+        scan[tid] += add;
+        __syncthreads();
+    }
+    double run = chunk_base + scan[tid] - local;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        double nxt = run + w[j];
+        if (w[j] > 0.0) {
+            atomicMax(&pick_hi, i0 + j);
+            if (nxt > t) atomicMin(&pick_lo, i0 + j);
+        }
+        run = nxt;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int tok = pick_lo != 0x7fffffff ? pick_lo : pick_hi;   // pick_hi: rounding at the chunk's end
+        a.out_tokens[(int64_t)b * (a.gmax + 1) + n] = tok;
+    }
+}
+
+}  // namespace
+
+size_t accept_workspace_bytes(int B, int gmax, int V)
+{
+    Ws w = carve(nullptr, B, gmax, V);
+    return reinterpret_cast<size_t>(w.wsum) + align256((size_t)B * w.nch * 2 * sizeof(double));
+}
+
+hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
+{
+    Ws ws = carve(a.workspace, a.B, a.gmax, a.V);
+    dim3 blk(kThreads);
+    hipLaunchKernelGGL(accept_row_stats, dim3(ws.nch, 2 * a.gmax + 1, a.B), blk, 0, stream, a, ws);
+    if (a.gmax > 0)
+        hipLaunchKernelGGL(accept_shifted_stats, dim3(ws.nch, a.gmax, a.B), blk, 0, stream, a, ws);
+    hipLaunchKernelGGL(accept_decide, dim3(a.B), blk, 0, stream, a, ws);
+    hipLaunchKernelGGL(accept_residual_sums, dim3(ws.nch, a.B), blk, 0, stream, a, ws);
+    hipLaunchKernelGGL(accept_draw, dim3(a.B), blk, 0, stream, a, ws);
+    return hipGetLastError();
+}

@@ -1,0 +1,219 @@
+// C ABI of librapid.so: argument checking, split planning, kernel dispatch.
+#include <new>
+
+#include "rapid_internal.h"
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int hip_fail(rapid_ctx* ctx, hipError_t e)
+{
+    if (ctx) ctx->last_hip_error = (int)e;
+    return RAPID_EHIP;
+}
+
+int check_attn_shape(const rapid_attn_shape* s)
+{
+    if (!s) return RAPID_EINVAL;
+    if (s->batch < 1 || s->q_max < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->max_ctx < 1) return RAPID_EINVAL;
+    if (s->n_q_heads % s->n_kv_heads) return RAPID_EINVAL;
+    if (s->gamma < 0 || s->gamma >= s->q_max || s->max_ctx < s->q_max) return RAPID_EINVAL;
+    if (!(s->softmax_scale > 0.f)) return RAPID_EINVAL;
+    if (s->chunk_tokens < 0) return RAPID_EINVAL;
+    if (s->head_dim != 64 && s->head_dim != 128) return RAPID_EUNSUPPORTED;
+    const int G = s->n_q_heads / s->n_kv_heads;
+    if ((int64_t)s->q_max * G > 80) return RAPID_EUNSUPPORTED;
+    if (s->page_size != 0) {
+        if (s->page_size < 16 || (s->page_size & (s->page_size - 1))) return RAPID_EUNSUPPORTED;
+        if (s->max_pages < 1 || (int64_t)s->max_pages * s->page_size < s->max_ctx) return RAPID_EINVAL;
+        if (s->kv_page_stride % 8) return RAPID_EALIGN;
+    } else if (s->kv_batch_stride % 8) {
+        return RAPID_EALIGN;
+    }
+    if (s->kv_token_stride < s->head_dim || s->kv_token_stride % 8 || s->kv_head_stride % 8) return RAPID_EALIGN;
+    // rows of one (sequence, head) are addressed with 32-bit byte offsets
+    const int64_t span_tokens = s->page_size ? s->page_size : s->max_ctx;
+    if (s->kv_token_stride * 2 * span_tokens >= (int64_t)1 << 32) return RAPID_EUNSUPPORTED;
+    return RAPID_OK;
+}
+
+// Tokens per KV split: a multiple of 128 chosen so that the grid has about four
+// workgroups per compute unit when every sequence is max_ctx long (ragged batches
+// then still balance), but never so small that a split is only a few tiles.
+int plan_chunk(const rapid_ctx* ctx, const rapid_attn_shape* s)
+{
+    const int quantum = 128;
+    if (s->chunk_tokens > 0) return (s->chunk_tokens + quantum - 1) / quantum * quantum;
+    const int n_cu = ctx ? ctx->n_cu : 256;
+    const int64_t units = (int64_t)s->batch * s->n_kv_heads;
+    const int64_t target_wg = s->batch > 1 ? 4LL * n_cu : 1LL * n_cu;
+    int64_t splits = (target_wg + units - 1) / units;
+    if (splits < 1) splits = 1;
+    int64_t chunk = (s->max_ctx + splits - 1) / splits;
+    chunk = (chunk + quantum - 1) / quantum * quantum;
+    if (chunk < 512) chunk = 512;
+    return (int)chunk;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rapid_create(rapid_ctx** out, int device)
+{
+    if (!out) return RAPID_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess) return RAPID_EHIP;
+    if (device < 0 || device >= n) return RAPID_EINVAL;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) return RAPID_EHIP;
+    rapid_ctx* c = new (std::nothrow) rapid_ctx;
+    if (!c) return RAPID_EINVAL;
+    c->device = device;
+    c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    c->last_hip_error = 0;
+    *out = c;
+    return RAPID_OK;
+}
+
+void rapid_destroy(rapid_ctx* ctx) { delete ctx; }
+
+const char* rapid_strerror(int status)
+{
+    switch (status) {
+        case RAPID_OK: return "ok";
+        case RAPID_EINVAL: return "invalid argument";
+        case RAPID_EALIGN: return "pointer or stride not aligned";
+        case RAPID_EUNSUPPORTED: return "shape not supported";
+        case RAPID_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case RAPID_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int rapid_last_hip_error(const rapid_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+int rapid_verify_attn_chunk(const rapid_ctx* ctx, const rapid_attn_shape* shape)
+{
+    int rc = check_attn_shape(shape);
+    if (rc != RAPID_OK) return rc;
+    return plan_chunk(ctx, shape);
+}
+
+size_t rapid_verify_attn_workspace_bytes(const rapid_ctx* ctx, const rapid_attn_shape* shape)
+{
+    if (check_attn_shape(shape) != RAPID_OK) return 0;
+    const int chunk = plan_chunk(ctx, shape);
+    const int nsplit = (shape->max_ctx + chunk - 1) / chunk;
+    const int G = shape->n_q_heads / shape->n_kv_heads;
+    const int RB = (shape->q_max * G + 15) / 16;
+    return attn_workspace_bytes(shape->batch, shape->n_kv_heads, nsplit, RB, shape->head_dim);
+}
+
+int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
+                      const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* ctx_lens, const int32_t* gammas, const int32_t* page_table,
+                      void* out, float* lse_out,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx) return RAPID_EINVAL;
+    int rc = check_attn_shape(shape);
+    if (rc != RAPID_OK) return rc;
+    if (!q || !k_cache || !v_cache || !ctx_lens || !out) return RAPID_EINVAL;
+    if (shape->page_size != 0 && !page_table) return RAPID_EINVAL;
+    if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16)) return RAPID_EALIGN;
+    const size_t need = rapid_verify_attn_workspace_bytes(ctx, shape);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return RAPID_EWORKSPACE;
+
+    AttnLaunch a{};
+    a.q = static_cast<const uint16_t*>(q);
+    a.k = static_cast<const uint16_t*>(k_cache);
+    a.v = static_cast<const uint16_t*>(v_cache);
+    a.ctx_lens = ctx_lens;
+    a.gammas = gammas;
+    a.page_table = shape->page_size ? page_table : nullptr;
+    a.out = static_cast<uint16_t*>(out);
+    a.lse_out = lse_out;
+    a.B = shape->batch;
+    a.Qmax = shape->q_max;
+    a.Hq = shape->n_q_heads;
+    a.Hkv = shape->n_kv_heads;
+    a.G = a.Hq / a.Hkv;
+    a.D = shape->head_dim;
+    a.gamma = shape->gamma;
+    a.chunk = plan_chunk(ctx, shape);
+    a.nsplit = (shape->max_ctx + a.chunk - 1) / a.chunk;
+    a.RB = (a.Qmax * a.G + 15) / 16;
+    a.bstride = shape->kv_batch_stride;
+    a.tstride = shape->kv_token_stride;
+    a.hstride = shape->kv_head_stride;
+    a.pstride = shape->kv_page_stride;
+    a.max_pages = shape->max_pages;
+    a.page_shift = -1;
+    a.page_mask = 0;
+    if (shape->page_size) {
+        int sh = 0;
+        while ((1 << sh) < shape->page_size) ++sh;
+        a.page_shift = sh;
+        a.page_mask = shape->page_size - 1;
+    }
+    a.scale_log2e = shape->softmax_scale * 1.4426950408889634f;
+    const size_t rows = (size_t)a.B * a.Hkv * a.nsplit * a.RB * 16;
+    const size_t o_bytes = (rows * a.D * sizeof(float) + 255) / 256 * 256;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes);
+
+    hipError_t e = launch_verify_attn(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
+size_t rapid_accept_workspace_bytes(const rapid_ctx*, int batch, int gamma_max, int vocab)
+{
+    if (batch < 1 || gamma_max < 0 || vocab < 1) return 0;
+    return accept_workspace_bytes(batch, gamma_max, vocab);
+}
+
+int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
+                 const float* target_logits, const float* draft_logits,
+                 const int32_t* draft_tokens, const int32_t* gammas,
+                 float eta, float temperature, float tail_alpha,
+                 const float* uniforms,
+                 int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
+                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx || batch < 1 || gamma_max < 0 || vocab < 1) return RAPID_EINVAL;
+    if (!target_logits || !uniforms || !n_accepted || !out_tokens) return RAPID_EINVAL;
+    if (gamma_max > 0 && (!draft_logits || !draft_tokens)) return RAPID_EINVAL;
+    if (!(eta >= 0.f) || !(temperature > 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
+    if (!aligned(target_logits, 4) || !aligned(draft_logits, 4)) return RAPID_EALIGN;
+    const size_t need = accept_workspace_bytes(batch, gamma_max, vocab);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return RAPID_EWORKSPACE;
+
+    AcceptLaunch a{};
+    a.zt = target_logits;
+    a.zd = draft_logits;
+    a.tokens = draft_tokens;
+    a.gammas = gammas;
+    a.uniforms = uniforms;
+    a.n_accepted = n_accepted;
+    a.out_tokens = out_tokens;
+    a.ratio = accept_ratio;
+    a.workspace = workspace;
+    a.B = batch;
+    a.gmax = gamma_max;
+    a.V = vocab;
+    a.eta = eta;
+    a.inv_T_exact = 1.0 / (double)temperature;
+    a.inv_T = (float)a.inv_T_exact;
+    a.tail_alpha = tail_alpha;
+    hipError_t e = launch_accept(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+// Internal declarations shared by the translation units of librapid.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "rapid.h"
+
+struct rapid_ctx {
+    int device;
+    int n_cu;
+    int last_hip_error;
+};
+
+// ---- verify attention (verify_attn.hip)
+struct AttnLaunch {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    const int32_t* ctx_lens;
+    const int32_t* gammas;
+    const int32_t* page_table;
+    uint16_t* out;
+    float* lse_out;
+    float* part_o;      // [B, Hkv, nsplit, RB*16, D] fp32, relative to part_m
+    float* part_ml;     // [B, Hkv, nsplit, RB*16, 2] (running max in log2 units, sum)
+    int32_t B, Qmax, Hq, Hkv, G, D, gamma;
+    int32_t chunk, nsplit, RB;
+    int64_t bstride, tstride, hstride, pstride;   // elements
+    int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
+    float scale_log2e;
+};
+hipError_t launch_verify_attn(const AttnLaunch& a, hipStream_t stream);
+size_t attn_workspace_bytes(int B, int Hkv, int nsplit, int RB, int D);
+
+// ---- accept pass (accept.hip)
+struct AcceptLaunch {
+    const float* zt;
+    const float* zd;
+    const int32_t* tokens;
+    const int32_t* gammas;
+    const float* uniforms;
+    int32_t* n_accepted;
+    int32_t* out_tokens;
+    float* ratio;
+    void* workspace;
+    int32_t B, gmax, V;
+    float eta, inv_T, tail_alpha;
+    double inv_T_exact;   // 1 / (double)temperature
+};
+hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
+size_t accept_workspace_bytes(int B, int gmax, int V);

@@ -1,0 +1,148 @@
+"""GPU parity: rapid_accept (C ABI, gfx950 kernels) against the float64 oracle.
+Accepted-prefix length and emitted tokens must match bit for bit, except
+sequences whose decisive accept test lies within 1e-5 of its uniform, or whose
+draw lands within 1e-5 (normalised) of a CDF edge; those are counted and printed."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_20330_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+gu = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    global gu
+    import gpu_util
+    gu = gpu_util
+    yield
+
+
+def check(cfg, acc, what, *, eta=None, temperature=None, tail_alpha=None, use_gammas=True, max_exempt_frac=0.2):
+    eta = cfg.eta if eta is None else eta
+    temperature = cfg.temperature if temperature is None else temperature
+    tail_alpha = cfg.tail_alpha if tail_alpha is None else tail_alpha
+    gpu, ref = gu.run_accept_case(acc, eta=eta, temperature=temperature, tail_alpha=tail_alpha, use_gammas=use_gammas)
+    st = gu.compare_accept(gpu, ref, acc.gammas if use_gammas else None, cfg.gamma_max)
+    print(f"[{what}] {st} mean_accepted={ref.n_accepted.mean():.2f}")
+    assert st["n_mismatch"] == 0 and st["token_mismatch"] == 0, st
+    assert st["exempt_sequences"] <= max(1, int(max_exempt_frac * st["sequences"])), st
+    assert st["max_ratio_rel_err"] < 1e-4, st
+    # shape of the token rows: accepted drafts, one drawn token in [0, V), then -1
+    n, tok, _ = gpu
+    for b in range(len(n)):
+        assert 0 <= tok[b, n[b]] < cfg.vocab
+        assert np.all(tok[b, n[b] + 1:] == -1)
+        np.testing.assert_array_equal(tok[b, :n[b]], acc.draft_tokens[b, :n[b]])
+    return gpu, ref, st
+
+
+def test_tiny_config():
+    cfg = wl.CONFIGS["tiny"]
+    check(cfg, wl.gen_accept_inputs(cfg), "tiny")
+
+
+def test_tiny_many_sequences_all_branches():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], draft_noise_std=1.5, gamma_choices=(0, 1, 2, 3, 4))
+    acc = wl.gen_accept_inputs(cfg, batch=256)
+    gpu, ref, st = check(cfg, acc, "tiny x256")
+    assert len(set(ref.n_accepted.tolist())) >= 4           # rejects at several positions and full accepts
+
+
+@pytest.mark.parametrize("V", [1, 2, 3, 5, 1023, 1024, 1025, 4099, 50257])
+def test_vocab_sizes_and_unaligned_rows(V):
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=V, draft_noise_std=1.0, gamma_choices=(3,))
+    check(cfg, wl.gen_accept_inputs(cfg, batch=16), f"V={V}", max_exempt_frac=0.5)
+
+
+@pytest.mark.parametrize("eta,T,alpha", [(0.0, 1.0, 0.1), (1.0, 1.0, 0.0), (5.0, 1.0, 0.1), (20.0, 1.0, 0.1),
+                                         (50.0, 1.0, 0.1), (5.0, 0.1, 0.1), (50.0, 0.1, 0.1), (2.0, 2.0, 0.3)])
+def test_eta_temperature_tail_sweep(eta, T, alpha):
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=32000, logit_std=2.0, draft_noise_std=0.7, temperature=T,
+                    gamma_choices=(5,))
+    check(cfg, wl.gen_accept_inputs(cfg, batch=48), f"eta={eta} T={T} alpha={alpha}", eta=eta, temperature=T,
+          tail_alpha=alpha)
+
+
+def test_identical_logits_accept_everything():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], draft_noise_std=0.0, gamma_choices=(4,))
+    acc = wl.gen_accept_inputs(cfg, batch=32)
+    gpu, ref, _ = check(cfg, acc, "identical logits", eta=3.0)
+    assert np.all(gpu[0] == 4) and np.allclose(gpu[2], 1.0, rtol=1e-5)
+
+
+def test_eta_zero_is_plain_speculative_sampling():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], draft_noise_std=1.0, gamma_choices=(4,))
+    acc = wl.gen_accept_inputs(cfg, batch=64)
+    gpu, ref, _ = check(cfg, acc, "eta=0", eta=0.0)
+    # ratio is p(x)/q(x) computed independently here from the logits
+    zt, zd = acc.target_logits.astype(np.float64), acc.draft_logits.astype(np.float64)
+    lp = zt - np.log(np.exp(zt - zt.max(-1, keepdims=True)).sum(-1, keepdims=True)) - zt.max(-1, keepdims=True)
+    lq = zd - np.log(np.exp(zd - zd.max(-1, keepdims=True)).sum(-1, keepdims=True)) - zd.max(-1, keepdims=True)
+    idx = acc.draft_tokens[..., None].astype(np.int64)
+    want = np.exp(np.take_along_axis(lp[:, :4], idx, -1) - np.take_along_axis(lq, idx, -1))[..., 0]
+    np.testing.assert_allclose(gpu[2], want, rtol=1e-4)
+
+
+def test_out_of_range_draft_token_is_rejected():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], draft_noise_std=0.0, gamma_choices=(4,))
+    acc = wl.gen_accept_inputs(cfg, batch=2)
+    acc.draft_tokens[0, 2] = cfg.vocab            # invalid id at position 2 of sequence 0
+    acc.draft_tokens[1, 0] = -7
+    dev = lambda a: torch.from_numpy(a).cuda()
+    n, tok, _ = gu.rapid().rapid_accept(dev(acc.target_logits), dev(acc.draft_logits), dev(acc.draft_tokens), 1.0,
+                                        dev(acc.uniforms))
+    torch.cuda.synchronize()
+    assert n.tolist() == [2, 0]
+    assert 0 <= tok[0, 2] < cfg.vocab and 0 <= tok[1, 0] < cfg.vocab
+
+
+def test_gamma_zero_only_draws_the_bonus():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], gamma_choices=(0,))
+    acc = wl.gen_accept_inputs(cfg, batch=8)
+    gpu, ref, _ = check(cfg, acc, "gamma=0")
+    assert np.all(gpu[0] == 0)
+
+
+def test_repeat_calls_are_identical():
+    cfg = wl.CONFIGS["llama8b_32k"]
+    acc = wl.gen_accept_inputs(cfg)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    args = (dev(acc.target_logits), dev(acc.draft_logits), dev(acc.draft_tokens), cfg.eta, dev(acc.uniforms))
+    a = [t.clone() for t in gu.rapid().rapid_accept(*args)]
+    b = [t.clone() for t in gu.rapid().rapid_accept(*args)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def test_bad_arguments_return_error_codes():
+    from paper_2502_20330_amd import binding
+    z = torch.zeros(1, 2, 8, device="cuda")
+    zd = torch.zeros(1, 1, 8, device="cuda")
+    t = torch.zeros(1, 1, dtype=torch.int32, device="cuda")
+    u = torch.zeros(1, 2, device="cuda")
+    for kw in (dict(eta=-1.0), dict(eta=1.0, temperature=0.0), dict(eta=1.0, tail_alpha=-0.5)):
+        eta = kw.pop("eta")
+        with pytest.raises(binding.RapidError) as e:
+            gu.rapid().rapid_accept(z, zd, t, eta, u, **kw)
+        assert e.value.status == -1
+
+
+# ---------------------------------------------------------------- full benchmark sizes
+def test_llama_vocab_full_size():
+    """Configs 2/3/5: one sequence, gamma = 8, V = 128256, eta = 1 (and 5's eta sweep)."""
+    cfg = wl.CONFIGS["llama8b_32k"]
+    acc = wl.gen_accept_inputs(cfg)
+    for eta in (1.0, 0.25, 0.5):
+        check(cfg, acc, f"V=128256 B=1 eta={eta}", eta=eta, max_exempt_frac=1.0)
+
+
+def test_llama_vocab_many_sequences():
+    """Same recipe, 64 seeded sequences with gamma in {4,6,8}: statistics of the exemptions."""
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"])
+    acc = wl.gen_accept_inputs(cfg, batch=64, salt=1)
+    gpu, ref, st = check(cfg, acc, "V=128256 B=64")
+    assert 0 < ref.n_accepted.mean() < acc.gammas.mean()        # both outcomes occur

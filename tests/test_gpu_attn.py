@@ -1,0 +1,187 @@
+"""GPU parity: rapid_verify_attn (C ABI, gfx950 kernels) against the float64 oracle,
+element by element, on seeded inputs that span several tiles, several KV splits
+and ragged tails.  Tolerance: |gpu - ref| <= 2e-2 + 1e-2*|ref| (bf16 in, fp32
+accumulate, bf16 out); max abs / max rel errors are printed."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_20330_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+gu = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    global gu
+    import gpu_util
+    gu = gpu_util
+    yield
+
+
+def check(cfg, inp=None, what="", **kw):
+    inp = inp or wl.gen_attn_inputs(cfg)
+    got, ref, lse, ref_lse = gu.run_attn_case(cfg, inp, **kw)
+    s = inp.seqs
+    e_abs, e_rel = gu.assert_attn_close(got, ref, what or cfg.name)
+    for b in range(cfg.batch):
+        Q = int(s.gammas[b]) + 1
+        assert np.all(got[b, Q:] == 0.0), "padded query rows must be zero"
+        np.testing.assert_allclose(lse[b, :, :Q], ref_lse[b, :, :Q], rtol=2e-3, atol=2e-3)
+    print(f"[{what or cfg.name}] max_abs={e_abs:.3e} max_rel={e_rel:.3e}")
+    return got, ref
+
+
+def test_tiny_config():
+    check(wl.CONFIGS["tiny"])
+
+
+@pytest.mark.parametrize("L", [5, 6, 31, 32, 33, 37, 127, 128, 129, 160, 511, 512, 513, 1000])
+def test_tile_and_split_edges(L):
+    cfg = wl.scaled(wl.CONFIGS["tiny"], ctx=(L, L), name=f"edge_L{L}")
+    check(cfg, chunk_tokens=128)
+
+
+@pytest.mark.parametrize("chunk", [0, 128, 256, 640, 4096])
+def test_split_count_does_not_change_result(chunk):
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(4133, 4133), name=f"l8b_4133_chunk{chunk}")
+    check(cfg, chunk_tokens=chunk)
+
+
+def test_peaked_softmax_unscaled_keys():
+    # K not pre-scaled: scores have std ~1 after 1/sqrt(d), softmax is far from uniform
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(3000, 3000), k_scale=1.0, name="peaked")
+    got, ref = check(cfg)
+    assert np.abs(ref).max() > 0.1
+
+
+def test_sharp_softmax_large_scale():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], ctx=(700, 700), name="sharp")
+    check(cfg, scale=1.0)            # scores N(0, 64): one key dominates most rows
+
+
+def test_needle_key():
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(2500, 2500), name="needle")
+    inp = wl.gen_attn_inputs(cfg)
+    qf = wl.bf16_bits_to_f32(inp.q)
+    # key 1234 of kv head 3 is aligned with query (pos 2, head 13): score +~20 after scaling
+    qv = qf[0, 2, 13]
+    target = qv * np.float32(20.0 * math.sqrt(128) / float(qv @ qv))
+    inp.k[0, 1234, 3] = wl.f32_to_bf16_bits(target)
+    got, ref = check(cfg, inp)
+    vf = wl.bf16_bits_to_f32(inp.v)[0, 1234, 3]
+    assert np.abs(ref[0, 2, 13] - vf).max() < 0.1
+
+
+@pytest.mark.parametrize("hq,hkv,gam", [(64, 8, 8), (8, 8, 8), (16, 8, 4), (24, 8, 2), (8, 1, 9), (4, 4, 0)])
+def test_group_sizes_and_gammas(hq, hkv, gam):
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], n_q_heads=hq, n_kv_heads=hkv, gamma_choices=(gam,),
+                    ctx=(1300, 1300), name=f"g{hq // hkv}_gamma{gam}")
+    check(cfg, chunk_tokens=512)
+
+
+def test_head_dim_64_multi_split():
+    cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=16, n_kv_heads=4, ctx=(5000, 5000), name="d64")
+    check(cfg, chunk_tokens=1024)
+
+
+def test_ragged_batch_contiguous():
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], paged=False, batch=5, ctx=(200, 3000), name="ragged_contig")
+    check(cfg, chunk_tokens=512)
+
+
+def test_ragged_batch_paged():
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], batch=6, ctx=(100, 3500), name="ragged_paged_small")
+    inp = wl.gen_attn_inputs(cfg)
+    assert len(set(inp.seqs.gammas.tolist())) > 1
+    check(cfg, inp, chunk_tokens=512)
+
+
+def test_paged_page_size_64():
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], batch=3, ctx=(900, 2000), page_size=64, name="paged64")
+    check(cfg, chunk_tokens=256)
+
+
+def test_head_major_cache_strides():
+    """Same data in a [B, Hkv, L, d] cache: only the strides differ."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(1500, 1500), name="head_major")
+    inp = wl.gen_attn_inputs(cfg)
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    ctx = torch.from_numpy(inp.seqs.ctx_lens).cuda()
+    base = gu.rapid().rapid_verify_attn(q, k, v, ctx, softmax_scale=cfg.softmax_scale)
+    kh = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    vh = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert kh.stride() != k.stride()
+    alt = gu.rapid().rapid_verify_attn(q, kh, vh, ctx, softmax_scale=cfg.softmax_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(base, alt)
+
+
+def test_cache_rows_past_ctx_len_are_never_used():
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(1111, 1111), name="tail_nan")
+    inp = wl.gen_attn_inputs(cfg)
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    pad = torch.full((1, 300, 8, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    k2, v2 = torch.cat([k, pad], 1), torch.cat([v, pad], 1)
+    ctx = torch.from_numpy(inp.seqs.ctx_lens).cuda()
+    a = gu.rapid().rapid_verify_attn(q, k, v, ctx, softmax_scale=cfg.softmax_scale, chunk_tokens=512)
+    b = gu.rapid().rapid_verify_attn(q, k2, v2, ctx, softmax_scale=cfg.softmax_scale, chunk_tokens=512)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.isfinite(b.float()).all()
+
+
+def test_repeat_calls_are_bitwise_identical():
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(6000, 6000), name="determinism")
+    inp = wl.gen_attn_inputs(cfg)
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    ctx = torch.from_numpy(inp.seqs.ctx_lens).cuda()
+    outs = [gu.rapid().rapid_verify_attn(q, k, v, ctx, softmax_scale=cfg.softmax_scale).clone() for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_bad_arguments_return_error_codes():
+    from paper_2502_20330_amd import binding
+    r = gu.rapid()
+    q = torch.zeros(1, 2, 4, 128, dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros(1, 64, 1, 128, dtype=torch.bfloat16, device="cuda")
+    ctx = torch.tensor([64], dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.RapidError) as e:       # head_dim 96
+        r.rapid_verify_attn(q[..., :96].contiguous(), k[..., :96].contiguous(), k[..., :96].contiguous(), ctx)
+    assert e.value.status == -3
+    q80 = torch.zeros(1, 11, 8, 128, dtype=torch.bfloat16, device="cuda")    # 11*8 = 88 rows > 80
+    with pytest.raises(binding.RapidError) as e:
+        r.rapid_verify_attn(q80, k, k, ctx)
+    assert e.value.status == -3
+    with pytest.raises(binding.RapidError) as e:       # scale <= 0
+        r.rapid_verify_attn(q, k, k, ctx, softmax_scale=0.0)
+    assert e.value.status == -1
+    with pytest.raises(binding.RapidError) as e:       # misaligned cache pointer
+        flat = torch.zeros(64 * 128 + 8, dtype=torch.bfloat16, device="cuda")
+        r.rapid_verify_attn(q, flat[1:1 + 64 * 128].view(1, 64, 1, 128), flat[1:1 + 64 * 128].view(1, 64, 1, 128), ctx)
+    assert e.value.status == -2
+
+
+# ---------------------------------------------------------------- full benchmark sizes
+def test_llama8b_32k_full_size():
+    """Config 2 at its real size, every output element against the oracle."""
+    check(wl.CONFIGS["llama8b_32k"])
+
+
+def test_llama8b_128k_layers_full_size():
+    """Config 3 shape (L = 131072) in the launch configuration the benchmark times:
+    two of the 32 layers (first and last seed), every output element."""
+    cfg = wl.CONFIGS["llama8b_128k_step"]
+    for layer in (0, cfg.layers - 1):
+        inp = wl.gen_attn_inputs(cfg, layer=layer)
+        check(cfg, inp, what=f"{cfg.name}[layer {layer}]")
+
+
+def test_llama70b_128k_layer_full_size():
+    """Config 5 shape (64 query heads, group 8 -> 72 packed rows), one layer."""
+    cfg = wl.CONFIGS["llama70b_128k_step"]
+    check(cfg, wl.gen_attn_inputs(cfg, layer=0), what=f"{cfg.name}[layer 0]")
