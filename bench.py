@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the RAPID verification step on one MI355X.
+
+One step = the whole hot path over one batch of synthetic input: verify attention
+of all layers of the workload (each layer has its own bf16 KV cache resident in
+HBM) followed by one accept/resample pass over the full vocabulary.
+
+Default workload: the Llama-3-8B-shaped full verify step at 128K context,
+gamma = 8 (32 layers, 32 query / 8 kv heads, head_dim 128, vocabulary 128256),
+the configuration the headline metric is quoted on.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_128k_step")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
+    ap.add_argument("--chunk-tokens", type=int, default=0, help="KV split size override (0 = library's choice)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2, help="layers of attention the oracle is timed on")
+    return ap.parse_args()
+
+
+def profile_traffic(kernel_key: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
+    summary (profiles/*.txt, a line `traffic_bytes_per_launch[<key>]: N`), or None."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    pat = re.compile(r"traffic_bytes_per_launch\[" + re.escape(kernel_key) + r"\]:\s*([0-9.eE+]+)")
+    for name in sorted(os.listdir(pdir)):
+        if name.endswith((".txt", ".md")):
+            m = pat.search(open(os.path.join(pdir, name)).read())
+            if m:
+                return float(m.group(1))
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2502_20330_amd import binding
+    from paper_2502_20330_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.workload]
+    layers = args.layers or cfg.layers
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    r = binding.Rapid(0)
+    lib = r.lib
+
+    # ---------------------------------------------------------------- synthetic inputs, resident in HBM
+    seqs = wl.gen_sequences(cfg)
+    B, Q, Hq, Hkv, d = cfg.batch, cfg.q_max, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    ctx_lens = torch.from_numpy(seqs.ctx_lens).to(dev)
+    gammas = torch.from_numpy(seqs.gammas).to(dev)
+    page_table = torch.from_numpy(seqs.page_table).to(dev) if cfg.paged else None
+    kv_shape = (seqs.n_pages, cfg.page_size, Hkv, d) if cfg.paged else (B, seqs.max_ctx, Hkv, d)
+    ks, vs, qs = [], [], []
+    for layer in range(layers):
+        g = torch.Generator(device=dev)
+        g.manual_seed(1000 * wl.SEED_QKV + layer)
+        k = torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g)
+        if cfg.k_scale != 1.0:
+            k.mul_(cfg.k_scale)
+        ks.append(k)
+        vs.append(torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g))
+        qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
+    outs = [torch.empty_like(qs[0]) for _ in range(2)]
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.SEED_LOGITS)
+    gmax, V = cfg.gamma_max, cfg.vocab
+    zt = torch.randn((B, gmax + 1, V), device=dev, generator=g) * cfg.logit_std
+    if cfg.draft_noise_std is None:
+        zd = torch.randn((B, gmax, V), device=dev, generator=g) * cfg.logit_std
+    else:
+        zd = (zt[:, :gmax] + torch.randn((B, gmax, V), device=dev, generator=g) * cfg.draft_noise_std).contiguous()
+    # drafter's own samples (Gumbel-max) and the uniforms of the accept tests / the draw
+    gumbel = -torch.log(-torch.log(torch.rand((B, gmax, V), device=dev, generator=g).clamp_min(1e-20)))
+    draft_tokens = torch.argmax(zd / cfg.temperature + gumbel, dim=-1).to(torch.int32)
+    del gumbel
+    uniforms = torch.rand((B, gmax + 1), device=dev, generator=g)
+    n_acc = torch.empty(B, dtype=torch.int32, device=dev)
+    out_tok = torch.empty((B, gmax + 1), dtype=torch.int32, device=dev)
+    ratio = torch.empty((B, gmax), dtype=torch.float32, device=dev)
+
+    # ---------------------------------------------------------------- prepared C-ABI calls
+    shape = r.attn_shape(qs[0], ks[0], seqs.max_ctx, page_table=page_table, softmax_scale=cfg.softmax_scale,
+                         chunk_tokens=args.chunk_tokens)
+    chunk = r.verify_attn_chunk(shape)
+    ws_attn = lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape))
+    ws_acc = lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V)
+    ws = torch.empty(max(ws_attn, ws_acc, 256), dtype=torch.uint8, device=dev)
+    stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    P = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
+    attn_args = [(r._ctx, ctypes.byref(shape), P(qs[l]), P(ks[l]), P(vs[l]), P(ctx_lens), P(gammas), P(page_table),
+                  P(outs[l & 1]), None, P(ws), ws.numel(), stream) for l in range(layers)]
+    acc_args = (r._ctx, B, gmax, V, P(zt), P(zd), P(draft_tokens), P(gammas), float(cfg.eta),
+                float(cfg.temperature), float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), P(ratio),
+                P(ws), ws.numel(), stream)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(f"librapid status {rc}: {lib.rapid_strerror(rc).decode()}")
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        for a in attn_args:
+            check(lib.rapid_verify_attn(*a))
+        if ev:
+            ev[1].record()
+        check(lib.rapid_accept(*acc_args))
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t_begin = torch.cuda.Event(enable_timing=True)
+    t_end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_begin.record()
+    for s in range(args.steps):
+        step(evs[s])
+    t_end.record()
+    torch.cuda.synchronize()
+    total_ms = t_begin.elapsed_time(t_end)
+    ms_per_step = total_ms / args.steps
+    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps      # all layers of one step
+    acc_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+
+    tokens = int(seqs.ctx_lens.astype(np.int64).sum())
+    kv_bytes_layer = tokens * cfg.kv_bytes_per_token()                    # algorithmic: K and V read once
+    kv_bytes_step = kv_bytes_layer * layers
+    logit_bytes = int(sum((2 * int(gb) + 1) * V * 4 for gb in seqs.gammas))
+    value = kv_bytes_step / (ms_per_step * 1e-3) / 1e9
+    attn_launch_ms = attn_ms / layers
+    attn_gbps = kv_bytes_layer / (attn_launch_ms * 1e-3) / 1e9
+    acc_gbps = logit_bytes / (acc_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "verify-step effective KV GB/s at 128K ctx, gamma=8 (verify-step us in verify_step_us)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "verify_step_us": round(ms_per_step * 1e3, 1),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": d, "ctx_tokens": tokens, "gamma": gmax, "vocab": V, "eta": cfg.eta,
+                   "kv_layout": "paged16" if cfg.paged else "[B,L,Hkv,d]", "chunk_tokens": chunk,
+                   "kv_bytes_per_step": kv_bytes_step},
+        "hbm_frac_of_peak": round(value / HBM_PEAK_GBPS, 4),
+        "breakdown_us": {"attention_all_layers": round(attn_ms * 1e3, 1),
+                         "attention_per_layer": round(attn_launch_ms * 1e3, 2), "accept": round(acc_ms * 1e3, 2)},
+        "roofline": {"bound": "hbm", "kernel": "verify_attn (split-KV + merge, per layer)",
+                     "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": kv_bytes_layer,
+                     "traffic": profile_traffic("verify_attn")},
+        "roofline_accept": {"bound": "hbm", "kernel": "rapid_accept (all kernels of one call)",
+                            "achieved": round(acc_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": round(acc_gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes_per_launch": logit_bytes,
+                            "traffic": profile_traffic("rapid_accept")},
+    }
+
+    # ---------------------------------------------------------------- oracle on the host cores (baseline only)
+    if not args.no_cpu_baseline:
+        import oracle
+        nl = max(1, min(args.cpu_layers, layers))
+        to_bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        bs, ts, hs, ps = wl.kv_strides(cfg, seqs)
+        lay = oracle.KVLayout(bs, ts, hs, cfg.page_size if cfg.paged else 0, ps,
+                              seqs.page_table.shape[1] if cfg.paged else 0)
+        host = [(to_bits(qs[l]), to_bits(ks[l]), to_bits(vs[l])) for l in range(nl)]
+        acc_host = (zt.cpu().numpy(), zd.cpu().numpy(), draft_tokens.cpu().numpy(), uniforms.cpu().numpy())
+        worst = 0.0
+        t0 = time.perf_counter()
+        refs = [oracle.verify_attn(q, k, v, seqs.ctx_lens, lay, Hkv=Hkv, scale=cfg.softmax_scale,
+                                   gammas=seqs.gammas, page_table=seqs.page_table) for q, k, v in host]
+        ref_acc = oracle.accept(*acc_host[:3], acc_host[3], eta=cfg.eta, temperature=cfg.temperature,
+                                tail_alpha=cfg.tail_alpha, gammas=seqs.gammas)
+        cpu_s = time.perf_counter() - t0
+        for l in range(nl):             # parity of the timed launch configuration, for the record
+            check(lib.rapid_verify_attn(*attn_args[l]))
+            torch.cuda.synchronize()
+            got = wl.bf16_bits_to_f32(to_bits(outs[l & 1])).astype(np.float64)
+            worst = max(worst, float(np.max(np.abs(got - refs[l]) - 1e-2 * np.abs(refs[l]))))
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        result["cpu_baseline"] = {
+            "value": round(kv_bytes_layer * nl / cpu_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{nl} of {layers} layers of verify attention (all heads, all {Q} positions, "
+                      f"{tokens} tokens) + the accept pass, float64, {cpu_s:.1f} s",
+            "gpu_vs_oracle_max_abs_err_minus_1e-2_rel": round(worst, 6),
+            "accept_matches_oracle": bool(np.array_equal(out_tok.cpu().numpy(), ref_acc.out_tokens)),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
