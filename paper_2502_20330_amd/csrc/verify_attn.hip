@@ -10,15 +10,21 @@
 //    are packed into the N side of bf16 MFMA tiles, so every K/V byte is read
 //    from HBM once and used by all R rows.
 //  * One workgroup = one (sequence, kv head, KV split).  Its four waves run
-//    independent software pipelines over interleaved 32-token tiles: coalesced
-//    128-bit global loads two tiles ahead into registers, a private LDS staging
-//    tile per wave (no workgroup barrier in the main loop), MFMA 16x16x32 bf16
-//    for S^T = K Q^T and O^T = V^T P^T with fp32 accumulators.
-//  * Scores are produced transposed (tokens on M, query rows on N): a query
-//    row's running max/sum then lives in one lane column, so the online softmax
-//    needs two cross-lane steps per tile instead of a butterfly per row.
-//  * V is stored token-major but the PV product reduces over tokens; the LDS V
-//    tile is XOR-swizzled so the per-lane column gathers are conflict free.
+//    independent pipelines over interleaved 32-token tiles.  K and V tiles travel
+//    HBM -> LDS directly (global_load_lds_dwordx4, 1 KiB per instruction, no
+//    staging registers) into a private two-slot ring per wave, two tiles ahead of
+//    the math; the wave waits on its own load counter, so the main loop has no
+//    workgroup barrier.
+//  * The lane -> global-chunk assignment of those loads applies an XOR swizzle,
+//    so that the later LDS reads (128-bit rows for K, transposed 64-bit reads for
+//    V) are bank-conflict free without padding.
+//  * Scores are produced transposed (S^T = K Q^T: tokens on M, query rows on N): a
+//    query row's running max/sum then lives in one lane column, so the online
+//    softmax needs two cross-lane steps per tile instead of a butterfly per row.
+//    The running max is only moved when it grows by more than 2^8, so the
+//    accumulator rescale almost never runs.
+//  * V is token-major in memory but the PV product reduces over tokens:
+//    ds_read_b64_tr_b16 delivers the transposed MFMA operand straight from LDS.
 //  * Waves combine (m, l, O) through LDS in a fixed order; the workgroup writes
 //    one fp32 partial.  A second small kernel merges the splits with the
 //    log-sum-exp rule and rounds to bf16.
@@ -32,44 +38,48 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
-constexpr int kTile = 32;          // tokens per wave tile
-constexpr int kWaves = 4;          // waves per workgroup
-constexpr int kChunkQuantum = kTile * kWaves;
+constexpr int kTile = 32;              // tokens per wave tile
+constexpr int kWaves = 4;              // waves per workgroup
 constexpr float kRescaleLog2 = 8.0f;   // lazy rescale threshold (log2 units)
 
 template <int D>
 struct Geo {
     static constexpr int KS = D / 32;             // MFMA k-steps of the QK product
     static constexpr int DB = D / 16;             // 16-wide blocks of the head dim (PV M side)
-    static constexpr int CPR = D * 2 / 16;        // 16-byte chunks per row
-    static constexpr int RPI = 64 / CPR;          // rows covered by one wave-wide 16-byte load
-    static constexpr int NLD = kTile / RPI;       // loads per tile per tensor
-    static constexpr int KROW = D * 2 + 16;       // padded LDS row of the K tile (bytes)
-    static constexpr int VROW = D * 2;            // LDS row of the swizzled V tile (bytes)
-    static constexpr int WAVE_LDS = kTile * (KROW + VROW);
+    static constexpr int ROWB = D * 2;            // bytes of one K or V row
+    static constexpr int CPR = ROWB / 16;         // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;          // rows moved by one wave-wide 1 KiB load
+    static constexpr int NLD = kTile / RPI;       // load instructions per tile per tensor
+    static constexpr int SLOT = kTile * ROWB;     // bytes of one K or V tile
+    static constexpr int WAVE_LDS = 4 * SLOT;     // K ring (2 slots) + V ring (2 slots)
 };
 
 template <int D, int RB>
 constexpr int attn_lds_bytes()
 {
     constexpr int tiles = kWaves * Geo<D>::WAVE_LDS;
-    constexpr int merge = (D * (RB * 16 + 1) + kWaves * RB * 16 * 2) * 4;
+    constexpr int merge = (2 * RB * 16 * (D + 4) + kWaves * RB * 16 * 2) * 4;
     return tiles > merge ? tiles : merge;
 }
 
-template <int D>
-struct TileRegs {
-    u32x4 k[Geo<D>::NLD];
-    u32x4 v[Geo<D>::NLD];
-};
+// LDS swizzles (16-byte chunk index within a row):
+//   K: chunk c of row r is stored at c ^ (r & 7)          -> 8 consecutive rows, same
+//      logical chunk, land in 8 different bank quads (ds_read_b128 operand loads);
+//   V: chunk c of row r is stored at c ^ 2*((r ^ (r>>2)) & 3) -> the four rows a
+//      transposed read gathers, and the rows of different 16-lane groups, spread
+//      over all banks.
+__device__ __forceinline__ int k_swz(int row) { return row & 7; }
+__device__ __forceinline__ int v_swz(int row) { return ((row ^ (row >> 2)) & 3) << 1; }
 
-// Where the rows of this (sequence, kv head) start.  Contiguous caches are addressed
-// as a wave-uniform base plus a 32-bit byte offset per lane (the host checks that a
-// sequence spans less than 4 GiB); paged caches look the page up per row.
+// Where the rows of this (sequence, kv head) start.  A wave-uniform base pointer
+// plus a 32-bit byte offset per lane (the host checks that a sequence, or a page,
+// spans less than 4 GiB); paged caches add a uniform page base per load.
 struct RowAddr {
     const char* kbase;
     const char* vbase;
-    const int32_t* pages;      // page table row of this sequence (paged only)
+    // page table row of this sequence (paged only), read through the constant address
+    // space so that the uniform lookups become scalar loads
+    const __attribute__((address_space(4))) int32_t* pages;
     uint32_t tok_bytes;        // bytes between consecutive tokens
     int64_t page_bytes;        // bytes between pages
     int page_shift, page_mask;
@@ -82,7 +92,7 @@ __device__ __forceinline__ RowAddr make_row_addr(const AttnLaunch& a, int b, int
     int64_t head = (int64_t)hkv * a.hstride + (PAGED ? 0 : (int64_t)b * a.bstride);
     r.kbase = reinterpret_cast<const char*>(a.k + head);
     r.vbase = reinterpret_cast<const char*>(a.v + head);
-    r.pages = PAGED ? a.page_table + (int64_t)b * a.max_pages : nullptr;
+    r.pages = PAGED ? (const __attribute__((address_space(4))) int32_t*)(a.page_table + (int64_t)b * a.max_pages) : nullptr;
     r.tok_bytes = (uint32_t)(a.tstride * 2);
     r.page_bytes = a.pstride * 2;
     r.page_shift = a.page_shift;
@@ -90,82 +100,96 @@ __device__ __forceinline__ RowAddr make_row_addr(const AttnLaunch& a, int b, int
     return r;
 }
 
-// Issue the global loads of one 32-token tile (K and V rows of this kv head).
-// Rows past `last_tok` are clamped to it; the softmax masks them.
-template <int D, bool PAGED>
-__device__ __forceinline__ void load_tile(TileRegs<D>& r, const RowAddr& ra, int t0, int last_tok, int lane)
+// Issue the HBM -> LDS loads of one 32-token tile of K or of V into `slot`
+// (wave-uniform LDS address).  Each instruction moves RPI whole rows: lane i
+// writes LDS bytes [16 i, 16 i + 16) of that 1 KiB block and fetches the global
+// chunk that the swizzle assigns to that position.  Rows past `last_tok` are
+// clamped to it (always a valid address); the softmax masks them.
+//
+// The instruction is written as inline assembly on purpose: the wave keeps its own
+// account of outstanding loads (wait_loads<N>() below).  Issued through the
+// compiler's builtin, every later LDS read would be preceded by a compiler-inserted
+// wait for ALL outstanding loads, which serialises the pipeline.
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+template <int D, bool PAGED, bool IS_V>
+__device__ __forceinline__ void dma_tile(const RowAddr& ra, uint32_t slot, int t0, int last_tok, int lane)
 {
     using G = Geo<D>;
-    const uint32_t lane_off = (lane % G::CPR) * 16;
+    const char* base = IS_V ? ra.vbase : ra.kbase;
+    const int r_local = lane / G::CPR, cpos = lane % G::CPR;
 #pragma unroll
     for (int e = 0; e < G::NLD; ++e) {
-        int tok = min(t0 + e * G::RPI + lane / G::CPR, last_tok);
+        const int row = e * G::RPI + r_local;
+        const int c = cpos ^ (IS_V ? v_swz(row) : k_swz(row));
+        const int tok = min(t0 + row, last_tok);
         if (PAGED) {
-            int64_t off = (int64_t)ra.pages[tok >> ra.page_shift] * ra.page_bytes
-                        + (uint32_t)(tok & ra.page_mask) * ra.tok_bytes + lane_off;
-            r.k[e] = *reinterpret_cast<const u32x4*>(ra.kbase + off);
-            r.v[e] = *reinterpret_cast<const u32x4*>(ra.vbase + off);
+            // the RPI rows of one instruction lie in one page (pages hold >= 16 tokens)
+            const int tok0 = min(t0 + e * G::RPI, last_tok);
+            const int64_t pg = ra.pages[tok0 >> ra.page_shift];
+            dma16(base + pg * ra.page_bytes, (uint32_t)(tok & ra.page_mask) * ra.tok_bytes + (uint32_t)c * 16u,
+                  slot + e * 1024);
         } else {
-            uint32_t off = (uint32_t)tok * ra.tok_bytes + lane_off;
-            r.k[e] = *reinterpret_cast<const u32x4*>(ra.kbase + off);
-            r.v[e] = *reinterpret_cast<const u32x4*>(ra.vbase + off);
+            dma16(base, (uint32_t)tok * ra.tok_bytes + (uint32_t)c * 16u, slot + e * 1024);
         }
     }
 }
 
-// V tile swizzle: the 32-byte column unit `u` of row `row` is stored at unit
-// u ^ ((row ^ (row >> 2)) & 3), which spreads both "rows r, r+4, r+8, r+12" and
-// "rows r..r+3" over distinct bank groups.
-__device__ __forceinline__ int v_swz(int row) { return (row ^ (row >> 2)) & 3; }
-
-template <int D>
-__device__ __forceinline__ void store_tile(const TileRegs<D>& r, char* kt, char* vt, int lane)
+// Wait until at most N of this wave's vector-memory loads are outstanding.  The
+// loads complete in order, so this guarantees everything older has landed in LDS.
+template <int N>
+__device__ __forceinline__ void wait_loads()
 {
-    using G = Geo<D>;
-#pragma unroll
-    for (int e = 0; e < G::NLD; ++e) {
-        int row = e * G::RPI + lane / G::CPR;
-        int c = lane % G::CPR;
-        *reinterpret_cast<u32x4*>(kt + row * G::KROW + c * 16) = r.k[e];
-        int pu = (c >> 1) ^ v_swz(row);
-        *reinterpret_cast<u32x4*>(vt + row * G::VROW + ((pu << 1) | (c & 1)) * 16) = r.v[e];
-    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// All LDS reads issued so far have returned: the slot they read may be refilled.
+__device__ __forceinline__ void lds_reads_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int D, int RB>
 struct WaveState {
-    float m[RB];                     // running max per query row, log2 units (score*scale*log2e)
+    float m[RB];                     // reference max per query row, log2 units (score*scale*log2e)
     float l[RB];                     // running sum, this lane group's tokens only
     floatx4 acc[Geo<D>::DB][RB];     // O^T: d = 16*db + 4*(lane/16) + i, row = 16*rb + lane%16
 };
 
-// One 32-token tile already staged in this wave's LDS region.
+// S^T[token][row] = sum_d K[token][d] Q[row][d] for the 32 tokens in `kt`.
 template <int D, int RB>
-__device__ __forceinline__ void compute_tile(WaveState<D, RB>& st, const bf16x8 (&qf)[RB][Geo<D>::KS],
-                                             const char* kt, char* vt, int t0, bool masked,
-                                             const int (&lim)[RB], float c, int lane)
+__device__ __forceinline__ void score_tile(floatx4 (&s)[2][RB], const bf16x8 (&qf)[RB][Geo<D>::KS],
+                                           const char* kt, int lane)
 {
     using G = Geo<D>;
     const int ln = lane & 15, lg = lane >> 4;
-    floatx4 s[2][RB];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) s[tb][rb] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    // S^T[token][row] = sum_d K[token][d] Q[row][d]
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
 #pragma unroll
+        for (int rb = 0; rb < RB; ++rb) s[tb][rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
-            bf16x8 ka = *reinterpret_cast<const bf16x8*>(kt + (tb * 16 + ln) * G::KROW + ks * 64 + lg * 16);
+            const int row = tb * 16 + ln;
+            const int c = (ks * 4 + lg) ^ k_swz(row);
+            bf16x8 ka = *reinterpret_cast<const bf16x8*>(kt + row * G::ROWB + c * 16);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 s[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[rb][ks], s[tb][rb], 0, 0, 0);
         }
     }
+}
+
+// Mask, online softmax with lazy rescale; leaves P^T packed as the B operand of PV.
+template <int D, int RB>
+__device__ __forceinline__ void softmax_tile(WaveState<D, RB>& st, floatx4 (&s)[2][RB], bf16x8 (&pb)[RB],
+                                             int t0, bool masked, const int (&lim)[RB], float c, int lane)
+{
+    using G = Geo<D>;
+    const int lg = lane >> 4;
     if (masked) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
@@ -177,7 +201,6 @@ __device__ __forceinline__ void compute_tile(WaveState<D, RB>& st, const bf16x8 
                     if (tok > lim[rb]) s[tb][rb][i] = -INFINITY;
                 }
     }
-
     float alpha[RB];
     bool changed = false;
 #pragma unroll
@@ -212,28 +235,32 @@ __device__ __forceinline__ void compute_tile(WaveState<D, RB>& st, const bf16x8 
 #pragma unroll
                 for (int i = 0; i < 4; ++i) st.acc[db][rb][i] *= alpha[rb];
     }
-
-    // P^T as the B operand: k-slot j of lane group lg is token 16*(j/4) + 4*lg + j%4,
-    // exactly the tokens this lane holds in s[j/4][rb][j%4].
-    bf16x8 pb[RB];
+    // k-slot j of lane group lg is token 16*(j/4) + 4*lg + j%4: exactly the tokens this
+    // lane holds in s[j/4][rb][j%4].
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int j = 0; j < 8; ++j) pb[rb][j] = (__bf16)s[j >> 2][rb][j & 3];
+}
 
-    // O^T[d][row] += sum_token V[token][d] P[row][token].  The A operand needs, per lane,
-    // eight tokens of one head-dim column; ds_read_b64_tr_b16 delivers four of them per
-    // read: inside a 16-lane group, lane i supplies the address of row i/4, columns
-    // 4*(i%4)..+3, and receives column i of rows 0..3.
+// O^T[d][row] += sum_token V[token][d] P[row][token].  The A operand needs, per lane,
+// eight tokens of one head-dim column; ds_read_b64_tr_b16 delivers four of them per
+// read: inside a 16-lane group, lane i supplies the address of row i/4, columns
+// 4*(i%4)..+3, and receives column i of rows 0..3.
+template <int D, int RB>
+__device__ __forceinline__ void pv_tile(WaveState<D, RB>& st, const bf16x8 (&pb)[RB], char* vt, int lane)
+{
+    using G = Geo<D>;
+    const int ln = lane & 15, lg = lane >> 4;
 #pragma unroll
     for (int db = 0; db < G::DB; ++db) {
         s16x4 half[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            int row = h * 16 + lg * 4 + (ln >> 2);
-            int pu = db ^ v_swz(row);
+            const int row = h * 16 + lg * 4 + (ln >> 2);
+            const int c = (db * 2) ^ v_swz(row);                 // chunk pair of the 32-byte column unit
             half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3)))*)(vt + row * G::VROW + pu * 32 + (ln & 3) * 8));
+                (s16x4 __attribute__((address_space(3)))*)(vt + row * G::ROWB + c * 16 + (ln & 3) * 8));
         }
         s16x8 both = __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
         bf16x8 va = __builtin_bit_cast(bf16x8, both);
@@ -248,7 +275,8 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
 {
     using G = Geo<D>;
     constexpr int RP = RB * 16;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kAhead = 3 * G::NLD;     // loads issued after the tile a wait is for
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
     const int L = a.ctx_lens[b];
@@ -260,6 +288,25 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ln = lane & 15, lg = lane >> 4;
+
+    const int ntile = (c1 - c0 + kTile - 1) / kTile;
+    const int nt = ntile > wave ? (ntile - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave
+    const int last_tok = c1 - 1;
+    auto tile_t0 = [&](int it) { return c0 + (wave + it * kWaves) * kTile; };
+    const RowAddr addr = make_row_addr<PAGED>(a, b, hkv);
+    char* kring = smem + wave * G::WAVE_LDS;
+    char* vring = kring + 2 * G::SLOT;
+    const uint32_t kring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * G::WAVE_LDS;
+    const uint32_t vring_lds = kring_lds + 2 * G::SLOT;
+
+    // Start the pipeline: tiles 0 and 1 of this wave.
+    if (nt > 0) {
+        dma_tile<D, PAGED, false>(addr, kring_lds, tile_t0(0), last_tok, lane);
+        dma_tile<D, PAGED, true>(addr, vring_lds, tile_t0(0), last_tok, lane);
+        dma_tile<D, PAGED, false>(addr, kring_lds + G::SLOT, tile_t0(1), last_tok, lane);
+        dma_tile<D, PAGED, true>(addr, vring_lds + G::SLOT, tile_t0(1), last_tok, lane);
+    }
+
 
     // Q^T as the B operand of the score product, kept in registers for the whole split.
     bf16x8 qf[RB][G::KS];
@@ -277,6 +324,16 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
             qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
         }
     }
+    // Retire the Q loads here, once (this also lands tiles 0 and 1, which iteration 0
+    // needs anyway): a wait for them inside the loop would drain the ring every tile.
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int ks = 0; ks < G::KS; ++ks) {
+            u32x4 raw = __builtin_bit_cast(u32x4, qf[rb][ks]);
+            asm volatile("" : "+v"(raw));
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
 
     WaveState<D, RB> st;
 #pragma unroll
@@ -286,38 +343,32 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
 #pragma unroll
         for (int db = 0; db < G::DB; ++db) st.acc[db][rb] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-
-    char* kt = smem + wave * G::WAVE_LDS;
-    char* vt = kt + kTile * G::KROW;
-    const int ntile = (c1 - c0 + kTile - 1) / kTile;
-    const int nt = ntile > wave ? (ntile - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave
-    const int last_tok = c1 - 1;
     const float c = a.scale_log2e;
     const int first_masked_t0 = min(L - Q, c1) - (kTile - 1);   // tiles with t0 >= this hold masked keys
-    auto tile_t0 = [&](int it) { return c0 + (wave + it * kWaves) * kTile; };
 
-    // Two tiles are always in flight.  Prefetches are unconditional (rows past the
-    // split are clamped to its last row and masked) and tiles go in pairs (a wave
-    // with an odd count runs one fully masked tile), so that the loop body has no
-    // branch and the load counters stay exact.
-    const RowAddr addr = make_row_addr<PAGED>(a, b, hkv);
-    if (nt > 0) {
-        TileRegs<D> ra, rb2;
-        load_tile<D, PAGED>(ra, addr, tile_t0(0), last_tok, lane);
-        load_tile<D, PAGED>(rb2, addr, tile_t0(1), last_tok, lane);
-        for (int it = 0; it < nt; it += 2) {
-            store_tile<D>(ra, kt, vt, lane);
-            load_tile<D, PAGED>(ra, addr, tile_t0(it + 2), last_tok, lane);
-            __builtin_amdgcn_wave_barrier();
-            compute_tile<D, RB>(st, qf, kt, vt, tile_t0(it), tile_t0(it) >= first_masked_t0, lim, c, lane);
-            __builtin_amdgcn_wave_barrier();
-            store_tile<D>(rb2, kt, vt, lane);
-            load_tile<D, PAGED>(rb2, addr, tile_t0(it + 3), last_tok, lane);
-            __builtin_amdgcn_wave_barrier();
-            compute_tile<D, RB>(st, qf, kt, vt, tile_t0(it + 1), tile_t0(it + 1) >= first_masked_t0, lim, c, lane);
-            __builtin_amdgcn_wave_barrier();
-        }
+    // Steady state, oldest load first: K(it) V(it) K(it+1) V(it+1).  Prefetches are
+    // unconditional (tiles past the split are clamped to its last row), so the
+    // number of loads behind the one being waited for is always 3*NLD.
+    for (int it = 0; it < nt; ++it) {
+        char* kt = kring + (it & 1) * G::SLOT;
+        char* vt = vring + (it & 1) * G::SLOT;
+        const int t0 = tile_t0(it);
+        floatx4 s[2][RB];
+        bf16x8 pb[RB];
+
+        wait_loads<kAhead>();                        // K(it) has landed
+        score_tile<D, RB>(s, qf, kt, lane);
+        lds_reads_done();
+        dma_tile<D, PAGED, false>(addr, kring_lds + (it & 1) * G::SLOT, tile_t0(it + 2), last_tok, lane);
+
+        softmax_tile<D, RB>(st, s, pb, t0, t0 >= first_masked_t0, lim, c, lane);
+
+        wait_loads<kAhead>();                        // V(it) has landed
+        pv_tile<D, RB>(st, pb, vt, lane);
+        lds_reads_done();
+        dma_tile<D, PAGED, true>(addr, vring_lds + (it & 1) * G::SLOT, tile_t0(it + 2), last_tok, lane);
     }
+    wait_loads<0>();                                 // no load may land after the ring is reused below
 
     // Row sums were kept per lane group; make them whole.
 #pragma unroll
@@ -326,10 +377,15 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
         st.l[rb] += __shfl_xor(st.l[rb], 32);
     }
 
-    // ---- combine the four waves (fixed order) and write the split's partial
-    __syncthreads();                                  // staging tiles are dead from here on
-    float* obuf = reinterpret_cast<float*>(smem);     // [D][RP+1]
-    float* mlbuf = obuf + D * (RP + 1);               // [kWaves][RP][2]
+    // ---- combine the four waves and write the split's partial.
+    // Waves 2 and 3 park their accumulators in LDS; waves 0 and 1 fold their partner's
+    // into their own (both brought to the workgroup's reference max) and write the
+    // pair sums back; then all threads add the two pair sums and store coalesced.
+    // The order of the additions is fixed, so results do not depend on timing.
+    __syncthreads();                                  // all rings are dead from here on
+    constexpr int OROW = D + 4;                       // padded row of the exchange buffers (floats)
+    float* obuf = reinterpret_cast<float*>(smem);     // [2][RP][OROW]
+    float* mlbuf = obuf + 2 * RP * OROW;              // [kWaves][RP][2]
     if (lg == 0) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -337,45 +393,50 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
             mlbuf[(wave * RP + rb * 16 + ln) * 2 + 1] = st.l[rb];
         }
     }
+    float* mine = obuf + (wave & 1) * RP * OROW;
+    if (wave >= 2) {
+#pragma unroll
+        for (int db = 0; db < G::DB; ++db)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                *reinterpret_cast<floatx4*>(mine + (rb * 16 + ln) * OROW + db * 16 + lg * 4) = st.acc[db][rb];
+    }
     __syncthreads();
     float m_all[RB], l_all[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        int row = rb * 16 + ln;
+        const int row = rb * 16 + ln;
+        float mw[kWaves];
         float mm = -INFINITY;
-        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, mlbuf[(w * RP + row) * 2]);
-        float m_use = (mm == -INFINITY) ? 0.f : mm;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            mw[w] = mlbuf[(w * RP + row) * 2];
+            mm = fmaxf(mm, mw[w]);
+        }
+        const float m_use = (mm == -INFINITY) ? 0.f : mm;
         float ll = 0.f;
-        for (int w = 0; w < kWaves; ++w)
-            ll += mlbuf[(w * RP + row) * 2 + 1] * fast_exp2(mlbuf[(w * RP + row) * 2] - m_use);
-        float f = fast_exp2(st.m[rb] - m_use);
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) ll += mlbuf[(w * RP + row) * 2 + 1] * fast_exp2(mw[w] - m_use);
         m_all[rb] = mm;
         l_all[rb] = ll;
+        if (wave < 2) {
+            const float f_own = fast_exp2(mw[wave] - m_use), f_par = fast_exp2(mw[wave + 2] - m_use);
 #pragma unroll
-        for (int db = 0; db < G::DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) st.acc[db][rb][i] *= f;
-    }
-    for (int w = 0; w < kWaves; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int db = 0; db < G::DB; ++db)
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        int idx = (db * 16 + lg * 4 + i) * (RP + 1) + rb * 16 + ln;
-                        if (w == 0) obuf[idx] = st.acc[db][rb][i];
-                        else obuf[idx] += st.acc[db][rb][i];
-                    }
+            for (int db = 0; db < G::DB; ++db) {
+                float* cell = mine + row * OROW + db * 16 + lg * 4;
+                floatx4 other = *reinterpret_cast<const floatx4*>(cell);
+                *reinterpret_cast<floatx4*>(cell) = st.acc[db][rb] * f_own + other * f_par;
+            }
         }
-        __syncthreads();
     }
+    __syncthreads();
     const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.nsplit + split) * RP;
-    float* po = a.part_o + pbase * D;
-    for (int idx = tid; idx < R * D; idx += kWaves * 64) {
-        int row = idx / D, d = idx % D;
-        po[idx] = obuf[d * (RP + 1) + row];
+    floatx4* po = reinterpret_cast<floatx4*>(a.part_o + pbase * D);
+    for (int f = tid; f < R * (D / 4); f += kWaves * 64) {
+        const int row = f / (D / 4), d4 = f % (D / 4);
+        const floatx4 x = *reinterpret_cast<const floatx4*>(obuf + row * OROW + d4 * 4);
+        const floatx4 y = *reinterpret_cast<const floatx4*>(obuf + (RP + row) * OROW + d4 * 4);
+        po[f] = x + y;
     }
     if (wave == 0 && lg == 0) {
 #pragma unroll
@@ -389,15 +450,16 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     }
 }
 
-// Merge the splits of one (sequence, kv head): out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Merge the splits of one query row: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// One workgroup of D threads per (sequence, kv head, packed row); the per-split
+// weights are formed once in LDS, then every thread sums its column over the splits.
 template <int D>
-__global__ void __launch_bounds__(256) verify_attn_merge(AttnLaunch a)
+__global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
 {
-    constexpr int ROWS = 256 / D;
-    const int hkv = blockIdx.y, b = blockIdx.z;
-    const int row = blockIdx.x * ROWS + threadIdx.x / D, d = threadIdx.x % D;
-    const int Rmax = a.Qmax * a.G;
-    if (row >= Rmax) return;
+    __shared__ float wgt[1024];
+    __shared__ float red[4];
+    const int row = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+    const int d = threadIdx.x;
     const int L = a.ctx_lens[b];
     const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
     const int R = Q * a.G, RP = a.RB * 16;
@@ -411,14 +473,47 @@ __global__ void __launch_bounds__(256) verify_attn_merge(AttnLaunch a)
     }
     const int ns = min((L + a.chunk - 1) / a.chunk, a.nsplit);
     const int64_t pbase = ((int64_t)b * a.Hkv + hkv) * a.nsplit * RP;
-    float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(pbase + (int64_t)s * RP + row) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < ns; ++s) {
-        int64_t pr = pbase + (int64_t)s * RP + row;
-        float w = fast_exp2(a.part_ml[pr * 2] - M);
-        den += w * a.part_ml[pr * 2 + 1];
-        num += w * a.part_o[pr * D + d];
+    float M = -INFINITY, den = 0.f, num = 0.f;
+    // splits in blocks of up to 1024 (one pass in practice), online over blocks
+    for (int s0 = 0; s0 < ns; s0 += 1024) {
+        const int nb = min(1024, ns - s0);
+        float mloc = -INFINITY;
+        for (int s = d; s < nb; s += D) mloc = fmaxf(mloc, a.part_ml[(pbase + (int64_t)(s0 + s) * RP + row) * 2]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, o));
+        __syncthreads();
+        if ((d & 63) == 0) red[d >> 6] = mloc;
+        __syncthreads();
+        float Mb = red[0];
+        for (int w = 1; w < D / 64; ++w) Mb = fmaxf(Mb, red[w]);
+        const float Mn = fmaxf(M, Mb);
+        const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
+        const float resc = fast_exp2(M - Mu);
+        num *= resc;
+        den *= resc;
+        M = Mn;
+        float dloc = 0.f;
+        for (int s = d; s < nb; s += D) {
+            int64_t pr = pbase + (int64_t)(s0 + s) * RP + row;
+            float w = fast_exp2(a.part_ml[pr * 2] - Mu);
+            wgt[s] = w;
+            dloc += w * a.part_ml[pr * 2 + 1];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dloc += __shfl_xor(dloc, o);
+        __syncthreads();
+        if ((d & 63) == 0) red[d >> 6] = dloc;
+        __syncthreads();
+        for (int w = 0; w < D / 64; ++w) den += red[w];
+        const float* po = a.part_o + (pbase + (int64_t)s0 * RP + row) * D + d;
+        float acc4[4] = {0.f, 0.f, 0.f, 0.f};
+        int s = 0;
+        for (; s + 4 <= nb; s += 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc4[j] += wgt[s + j] * po[(int64_t)(s + j) * RP * D];
+        }
+        for (; s < nb; ++s) acc4[0] += wgt[s] * po[(int64_t)s * RP * D];
+        num += (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
     }
     float o = den > 0.f ? num / den : 0.f;
     __bf16 ob = (__bf16)o;
@@ -476,9 +571,8 @@ hipError_t launch_verify_attn(const AttnLaunch& a, hipStream_t stream)
     else if (a.D == 64) e = paged ? dispatch_rb<64, true>(a, stream) : dispatch_rb<64, false>(a, stream);
     else return hipErrorInvalidValue;
     if (e != hipSuccess) return e;
-    const int rows_per_block = 256 / a.D;
-    dim3 grid((a.Qmax * a.G + rows_per_block - 1) / rows_per_block, a.Hkv, a.B);
-    if (a.D == 128) hipLaunchKernelGGL(verify_attn_merge<128>, grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(verify_attn_merge<64>, grid, dim3(256), 0, stream, a);
+    dim3 grid(a.Qmax * a.G, a.Hkv, a.B);
+    if (a.D == 128) hipLaunchKernelGGL(verify_attn_merge<128>, grid, dim3(128), 0, stream, a);
+    else hipLaunchKernelGGL(verify_attn_merge<64>, grid, dim3(64), 0, stream, a);
     return hipGetLastError();
 }
