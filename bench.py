@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--chunk-tokens", type=int, default=0, help="KV split size override (0 = library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers of attention the oracle is timed on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -138,6 +140,12 @@ def main():
         if ev:
             ev[2].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

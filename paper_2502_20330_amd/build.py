@@ -14,6 +14,9 @@ SOURCES = ["rapid_api.hip", "verify_attn.hip", "accept.hip"]
 # packed-fp32 instructions are switched off on purpose (build flags)
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep MFMA accumulators in ordinary VGPRs: the default AGPR form made the
+         # compiler shuttle ~450 registers per tile between the two files
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

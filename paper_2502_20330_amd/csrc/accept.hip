@@ -14,9 +14,10 @@
 //
 //   K1 row_stats      : per chunk (max z, sum exp((z - max)/T)) of every target and draft row
 //   K2 shifted_stats  : per chunk (max, sum exp) of d = (z - zmax)/T + eta (q - p)
-//   K3 decide         : combine chunks -> log-normalisers (double); accept tests in
-//                       double at the drafted tokens; first reject n; prefix of out_tokens
-//   K4 residual_sums  : per chunk sum of the draw weights of row n (double)
+//   K3 decide         : one wave per row: combine chunks -> log-normalisers (double), accept
+//                       test in double at the drafted token -> pass/fail flag, ratio
+//   K4 residual_sums  : n = first failed flag; per chunk sum of the draw weights of row n (double);
+//                       n_accepted and the accepted prefix of out_tokens
 //   K5 draw           : locate the chunk and the token where the running sum passes u*W
 //
 // Sums over the vocabulary run in fp32 per thread and are combined in fp64;
@@ -97,6 +98,7 @@ struct Ws {
     float2* st_h;     // [B][gmax][nch]    (max d, sum exp(d - max d)), d relative to the target row max / T
     double* rows;     // [B][gmax+1][8]: zmax_t, lse_p, zmax_d, lse_q, lse_h, 1/S_h (= max p_hat), -, -
     double* wsum;     // [B][nch][2]: sum of residual weights, sum of p (fallback)
+    int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
     int nch;
 };
 
@@ -112,6 +114,7 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
     w.st_h = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
     w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 8 * sizeof(double));
     w.wsum = reinterpret_cast<double*>(p); p += align256((size_t)B * w.nch * 2 * sizeof(double));
+    w.flags = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * sizeof(int32_t));
     return w;
 }
 
@@ -166,16 +169,16 @@ __global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a,
     const int ch = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
     if (k >= g) return;
+    const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
+    const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
+    const bool vec = ((reinterpret_cast<uintptr_t>(zt) & 15) == 0) && ((reinterpret_cast<uintptr_t>(zd) & 15) == 0);
+    const int i0 = ch * kChunk + threadIdx.x * 4;
+    floatx4 x = load4(zt, i0, a.V, vec), y = load4(zd, i0, a.V, vec);   // in flight while the row statistics combine
     double Mt, St, Md, Sd;
     combine_row(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Mt, St);
     combine_row(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Md, Sd);
     const float zmax_t = (float)Mt, zmax_d = (float)Md;       // exact: they are float values
     const float lnS_t = (float)log(St), lnS_d = (float)log(Sd);
-    const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
-    const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
-    const bool vec = ((reinterpret_cast<uintptr_t>(zt) & 15) == 0) && ((reinterpret_cast<uintptr_t>(zd) & 15) == 0);
-    const int i0 = ch * kChunk + threadIdx.x * 4;
-    floatx4 x = load4(zt, i0, a.V, vec), y = load4(zd, i0, a.V, vec);
     float d[4];
     float m = -INFINITY;
 #pragma unroll
@@ -197,56 +200,77 @@ __global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a,
 }
 
 // ---------------------------------------------------------------- K3
-__global__ void __launch_bounds__(kThreads) accept_decide(AcceptLaunch a, Ws ws)
+// One wave per (sequence, row): combine the row's per-chunk statistics in fp64 and
+// run the accept test of that row's drafted token.
+__device__ __forceinline__ void wave_combine(const float2* st, int nch, double inv_T, double& M, double& S)
 {
-    __shared__ double shd[8];
-    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    double m = -INFINITY;
+    for (int i = lane; i < nch; i += 64) m = fmax(m, (double)st[i].x);
+    M = wave_max(m);
+    double s = 0.0;
+    for (int i = lane; i < nch; i += 64) {
+        float2 v = st[i];
+        if (v.y > 0.f) s += (double)v.y * exp(((double)v.x - M) * inv_T);
+    }
+    S = wave_sum(s);
+}
+
+__global__ void __launch_bounds__(64) accept_decide(AcceptLaunch a, Ws ws)
+{
+    const int k = blockIdx.x, b = blockIdx.y;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
-    double* rows = ws.rows + (int64_t)b * (a.gmax + 1) * 8;
-    for (int k = 0; k <= g; ++k) {
-        double Mt, St;
-        combine_row(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Mt, St);
-        double Md = 0, Sd = 1, Mh = 0, Sh = 1;
-        if (k < g) {
-            combine_row(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Md, Sd);
-            combine_row(ws.st_h + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, 1.0, shd, Mh, Sh);
-        }
-        if (threadIdx.x == 0) {
-            double* r = rows + k * 8;
-            r[0] = Mt;                                   // raw max of the target row
-            r[1] = log(St);                              // lse_p = r[0]/T + r[1]
-            r[2] = Md;
-            r[3] = log(Sd);
-            r[4] = Mh + log(Sh);                         // lse_h = r[0]/T + r[4]
-            r[5] = 1.0 / Sh;                             // max p_hat
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x != 0) return;
-    __threadfence_block();
-    const double invT = (double)a.inv_T_exact;
-    int n = g;
-    int32_t* toks = a.out_tokens + (int64_t)b * (a.gmax + 1);
-    for (int k = 0; k < g; ++k) {
-        const double* r = rows + k * 8;
-        int x = a.tokens[(int64_t)b * a.gmax + k];
-        double rho = 0.0;
-        bool ok = false;
+    if (k > g) return;
+    // the drafted token's two logits are fetched while the statistics combine
+    int x = -1;
+    float zx_t = 0.f, zx_d = 0.f;
+    if (k < g) {
+        x = a.tokens[(int64_t)b * a.gmax + k];
         if (x >= 0 && x < a.V) {
-            double at = ((double)a.zt[((int64_t)b * (a.gmax + 1) + k) * a.V + x] - r[0]) * invT;
-            double ad = ((double)a.zd[((int64_t)b * a.gmax + k) * a.V + x] - r[2]) * invT;
-            double p = exp(at - r[1]), q = exp(ad - r[3]);
-            double ph = exp(at + (double)a.eta * (q - p) - r[4]);
-            if (ph < (double)a.tail_alpha * r[5]) ph = p;
-            rho = q > 0.0 ? ph / q : INFINITY;
-            double u = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + k];
-            ok = u <= fmin(1.0, rho);
+            zx_t = a.zt[((int64_t)b * (a.gmax + 1) + k) * a.V + x];
+            zx_d = a.zd[((int64_t)b * a.gmax + k) * a.V + x];
         }
-        if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
-        if (!ok && n == g) n = k;
     }
-    for (int k = 0; k <= a.gmax; ++k) toks[k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
-    a.n_accepted[b] = n;
+    double Mt, St, Md = 0, Sd = 1, Mh = 0, Sh = 1;
+    wave_combine(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, Mt, St);
+    if (k < g) {
+        wave_combine(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, Md, Sd);
+        wave_combine(ws.st_h + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, 1.0, Mh, Sh);
+    }
+    if (threadIdx.x != 0) return;
+    double* r = ws.rows + ((int64_t)b * (a.gmax + 1) + k) * 8;
+    const double lnS_t = log(St), lnS_d = log(Sd), lse_h = Mh + log(Sh), pmax = 1.0 / Sh;
+    r[0] = Mt;                                   // raw max of the target row
+    r[1] = lnS_t;                                // lse_p = r[0]/T + r[1]
+    r[2] = Md;
+    r[3] = lnS_d;
+    r[4] = lse_h;                                // lse_h = r[0]/T + r[4]
+    r[5] = pmax;                                 // max p_hat
+    if (k >= g) return;
+    double rho = 0.0;
+    bool ok = false;
+    if (x >= 0 && x < a.V) {
+        const double invT = a.inv_T_exact;
+        double at = ((double)zx_t - Mt) * invT;
+        double ad = ((double)zx_d - Md) * invT;
+        double p = exp(at - lnS_t), q = exp(ad - lnS_d);
+        double ph = exp(at + (double)a.eta * (q - p) - lse_h);
+        if (ph < (double)a.tail_alpha * pmax) ph = p;
+        rho = q > 0.0 ? ph / q : INFINITY;
+        double u = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + k];
+        ok = u <= fmin(1.0, rho);
+    }
+    if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
+    ws.flags[(int64_t)b * a.gmax + k] = ok ? 1 : 0;
+}
+
+// Number of accepted drafts: index of the first failed accept test, or g.
+__device__ __forceinline__ int first_reject(const Ws& ws, int b, int gmax, int g)
+{
+    int n = g;
+    for (int k = g - 1; k >= 0; --k)
+        if (ws.flags[(int64_t)b * gmax + k] == 0) n = k;
+    return n;
 }
 
 // Draw weight of vocabulary entry v of row n (fp64): the residual
@@ -288,7 +312,12 @@ __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a,
     __shared__ double shd[8];
     const int ch = blockIdx.x, b = blockIdx.y;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
-    const int n = a.n_accepted[b];
+    const int n = first_reject(ws, b, a.gmax, g);
+    if (ch == 0 && threadIdx.x <= a.gmax) {
+        const int k = threadIdx.x;               // accepted drafts, then -1 (the draw fills slot n later)
+        a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
+        if (k == 0) a.n_accepted[b] = n;
+    }
     RowCtx c = make_row_ctx(a, ws, b, n, g);
     double sw = 0.0, sp = 0.0;
     const int i0 = ch * kChunk + threadIdx.x * 4;
@@ -310,51 +339,85 @@ __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a,
 }
 
 // ---------------------------------------------------------------- K5
+// Prefix sums over the kThreads threads of a block (fp64); `sh` has >= 4 slots.
+// Returns the exclusive prefix; `incl` gets the inclusive one and `total` the block
+// sum.  incl of thread j and the exclusive prefix of thread j+1 are the same
+// floating-point value, so "first prefix above t" has exactly one owner.
+__device__ __forceinline__ double block_scan(double v, double* sh, double& incl, double& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double iw = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        double y = __shfl_up(iw, o);
+        if (lane >= o) iw += y;
+    }
+    double ew = __shfl_up(iw, 1);
+    if (lane == 0) ew = 0.0;
+    __syncthreads();
+    if (lane == 63) sh[wave] = iw;
+    __syncthreads();
+    double off = 0.0, tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < wave) off += sh[w];
+        tot += sh[w];
+    }
+    total = tot;
+    incl = off + iw;
+    return off + ew;
+}
+
 __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
 {
     __shared__ double shd[8];
-    __shared__ double scan[kThreads];
-    __shared__ int pick_chunk, pick_lo, pick_hi;
+    __shared__ int pick_chunk, last_chunk, pick_lo, pick_hi;
     __shared__ double chunk_base;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
-    const int n = a.n_accepted[b];
+    const int n = first_reject(ws, b, a.gmax, g);
     RowCtx c = make_row_ctx(a, ws, b, n, g);
     const double* cs = ws.wsum + (int64_t)b * ws.nch * 2;
+    if (tid == 0) { pick_chunk = -1; last_chunk = 0; pick_lo = 0x7fffffff; pick_hi = -1; }
 
-    double tw = 0.0;
-    for (int i = tid; i < ws.nch; i += kThreads) tw += cs[i * 2];
-    const double Wres = block_sum(tw, shd);
+    // every thread owns `per` consecutive chunks
+    const int per = (ws.nch + kThreads - 1) / kThreads;
+    const int cbeg = min(tid * per, ws.nch), cend = min(cbeg + per, ws.nch);
+    double tw = 0.0, tp = 0.0;
+    for (int i = cbeg; i < cend; ++i) { tw += cs[i * 2]; tp += cs[i * 2 + 1]; }
+    double Wres, Wp, in_w, in_p;
+    const double ex_w = block_scan(tw, shd, in_w, Wres);
+    const double ex_p = block_scan(tp, shd, in_p, Wp);
     const int col = Wres > 0.0 ? 0 : 1;          // empty residual: draw from p instead
-    double W = Wres;
-    if (col == 1) {
-        double tp = 0.0;
-        for (int i = tid; i < ws.nch; i += kThreads) tp += cs[i * 2 + 1];
-        W = block_sum(tp, shd);
-    }
+    const double W = col == 0 ? Wres : Wp;
     const double t = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + a.gmax] * W;
 
     // chunk whose inclusive running sum first exceeds t (chunks in vocabulary order)
-    if (tid == 0) {
-        double run = 0.0;
-        int pc = -1, last_pos = 0;
-        double base = 0.0;
-        for (int i = 0; i < ws.nch; ++i) {
-            double v = cs[i * 2 + col];
-            if (v > 0.0) last_pos = i;
-            if (pc < 0 && run + v > t) { pc = i; base = run; }
-            run += v;
+    {
+        const double excl = col == 0 ? ex_w : ex_p, incl = col == 0 ? in_w : in_p;
+        int lastpos = -1;
+        for (int i = cbeg; i < cend; ++i) if (cs[i * 2 + col] > 0.0) lastpos = i;
+        if (lastpos >= 0) atomicMax(&last_chunk, lastpos);
+        if (excl <= t && incl > t) {             // the crossing lies in this thread's chunks
+            double run = excl;
+            for (int i = cbeg; i < cend; ++i) {
+                double v = cs[i * 2 + col];
+                if (run + v > t || i == cend - 1) { pick_chunk = i; chunk_base = run; break; }
+                run += v;
+            }
         }
-        if (pc < 0) {                             // t rounded up to W
-            pc = last_pos;
-            base = run - cs[last_pos * 2 + col];
-        }
-        pick_chunk = pc;
-        chunk_base = base;
-        pick_lo = 0x7fffffff;
-        pick_hi = -1;
     }
     __syncthreads();
+    if (pick_chunk < 0) {                         // t rounded up to W: last chunk with weight
+        __syncthreads();
+        if (tid == 0) {
+            double base = 0.0;
+            for (int i = 0; i < last_chunk; ++i) base += cs[i * 2 + col];
+            pick_chunk = last_chunk;
+            chunk_base = base;
+        }
+        __syncthreads();
+    }
     const int i0 = pick_chunk * kChunk + tid * 4;
     double w[4], local = 0.0;
 #pragma unroll
@@ -367,16 +430,8 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
         }
         local += w[j];
     }
-    scan[tid] = local;
-    __syncthreads();
-    // exclusive prefix of the per-thread sums (Hillis-Steele over 256 entries)
-    for (int o = 1; o < kThreads; o <<= 1) {
-        double add = tid >= o ? scan[tid - o] : 0.0;
-        __syncthreads();
-        scan[tid] += add;
-        __syncthreads();
-    }
-    double run = chunk_base + scan[tid] - local;
+    double chunk_total, local_incl;
+    double run = chunk_base + block_scan(local, shd, local_incl, chunk_total);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         double nxt = run + w[j];
@@ -398,7 +453,7 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
 size_t accept_workspace_bytes(int B, int gmax, int V)
 {
     Ws w = carve(nullptr, B, gmax, V);
-    return reinterpret_cast<size_t>(w.wsum) + align256((size_t)B * w.nch * 2 * sizeof(double));
+    return reinterpret_cast<size_t>(w.flags) + align256((size_t)B * (gmax > 0 ? gmax : 1) * sizeof(int32_t));
 }
 
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
@@ -408,7 +463,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
     hipLaunchKernelGGL(accept_row_stats, dim3(ws.nch, 2 * a.gmax + 1, a.B), blk, 0, stream, a, ws);
     if (a.gmax > 0)
         hipLaunchKernelGGL(accept_shifted_stats, dim3(ws.nch, a.gmax, a.B), blk, 0, stream, a, ws);
-    hipLaunchKernelGGL(accept_decide, dim3(a.B), blk, 0, stream, a, ws);
+    hipLaunchKernelGGL(accept_decide, dim3(a.gmax + 1, a.B), dim3(64), 0, stream, a, ws);
     hipLaunchKernelGGL(accept_residual_sums, dim3(ws.nch, a.B), blk, 0, stream, a, ws);
     hipLaunchKernelGGL(accept_draw, dim3(a.B), blk, 0, stream, a, ws);
     return hipGetLastError();

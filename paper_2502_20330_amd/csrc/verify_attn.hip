@@ -10,7 +10,8 @@
 //    are packed into the N side of bf16 MFMA tiles, so every K/V byte is read
 //    from HBM once and used by all R rows.
 //  * One workgroup = one (sequence, kv head, KV split).  Its four waves run
-//    independent pipelines over interleaved 32-token tiles.  K and V tiles travel
+//    independent pipelines, each over its own contiguous quarter of the split in
+//    32-token tiles.  K and V tiles travel
 //    HBM -> LDS directly (global_load_lds_dwordx4, 1 KiB per instruction, no
 //    staging registers) into a private two-slot ring per wave, two tiles ahead of
 //    the math; the wave waits on its own load counter, so the main loop has no
@@ -278,7 +279,9 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     constexpr int kAhead = 3 * G::NLD;     // loads issued after the tile a wait is for
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+    // kv head fastest: the workgroups of one token range sit next to each other in
+    // dispatch order, so the cache lines of a token (all heads) are fetched together
+    const int hkv = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
     const int L = a.ctx_lens[b];
     const int c0 = split * a.chunk;
     if (c0 >= L) return;                             // this split holds no token of sequence b
@@ -290,9 +293,12 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     const int ln = lane & 15, lg = lane >> 4;
 
     const int ntile = (c1 - c0 + kTile - 1) / kTile;
-    const int nt = ntile > wave ? (ntile - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave
-    const int last_tok = c1 - 1;
-    auto tile_t0 = [&](int it) { return c0 + (wave + it * kWaves) * kTile; };
+    // each wave streams its own contiguous quarter of the split
+    const int ntq = (ntile + kWaves - 1) / kWaves;
+    const int nt = max(0, min(ntq, ntile - wave * ntq));                      // tiles of this wave
+    // last token this wave may load: prefetches past its range are clamped to this row
+    const int last_tok = min(c1, c0 + (wave + 1) * ntq * kTile) - 1;
+    auto tile_t0 = [&](int it) { return c0 + (wave * ntq + it) * kTile; };
     const RowAddr addr = make_row_addr<PAGED>(a, b, hkv);
     char* kring = smem + wave * G::WAVE_LDS;
     char* vring = kring + 2 * G::SLOT;
@@ -451,13 +457,16 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
 }
 
 // Merge the splits of one query row: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// One workgroup of D threads per (sequence, kv head, packed row); the per-split
-// weights are formed once in LDS, then every thread sums its column over the splits.
+// One workgroup of D threads per (sequence, kv head, packed row), splits taken 32 at a
+// time.  The kernel is latency bound, so every thread issues the loads of its column
+// for a whole block of splits before anything else, next to the (m, l) loads; the
+// weights are formed while they are in flight.
 template <int D>
 __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
 {
-    __shared__ float wgt[1024];
-    __shared__ float red[4];
+    constexpr int SB = 32;                             // splits per block
+    __shared__ float wgt[SB];
+    __shared__ float red[2][4];
     const int row = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
     const int d = threadIdx.x;
     const int L = a.ctx_lens[b];
@@ -474,46 +483,43 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
     const int ns = min((L + a.chunk - 1) / a.chunk, a.nsplit);
     const int64_t pbase = ((int64_t)b * a.Hkv + hkv) * a.nsplit * RP;
     float M = -INFINITY, den = 0.f, num = 0.f;
-    // splits in blocks of up to 1024 (one pass in practice), online over blocks
-    for (int s0 = 0; s0 < ns; s0 += 1024) {
-        const int nb = min(1024, ns - s0);
-        float mloc = -INFINITY;
-        for (int s = d; s < nb; s += D) mloc = fmaxf(mloc, a.part_ml[(pbase + (int64_t)(s0 + s) * RP + row) * 2]);
+    for (int s0 = 0; s0 < ns; s0 += SB) {
+        const int nb = min(SB, ns - s0);
+        const float* po = a.part_o + (pbase + (int64_t)s0 * RP + row) * D + d;
+        float o[SB];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, o));
+        for (int j = 0; j < SB; ++j) o[j] = j < nb ? po[(int64_t)j * RP * D] : 0.f;
+        float ms = -INFINITY, ls = 0.f;
+        if (d < nb) {
+            const float* ml = a.part_ml + (pbase + (int64_t)(s0 + d) * RP + row) * 2;
+            ms = ml[0];
+            ls = ml[1];
+        }
+        float mb = ms;                                 // D >= 64 > SB: the first wave holds them all
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) mb = fmaxf(mb, __shfl_xor(mb, off));
+        if (d == 0) red[0][0] = mb;
         __syncthreads();
-        if ((d & 63) == 0) red[d >> 6] = mloc;
-        __syncthreads();
-        float Mb = red[0];
-        for (int w = 1; w < D / 64; ++w) Mb = fmaxf(Mb, red[w]);
-        const float Mn = fmaxf(M, Mb);
+        mb = red[0][0];
+        const float Mn = fmaxf(M, mb);
         const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
         const float resc = fast_exp2(M - Mu);
-        num *= resc;
-        den *= resc;
         M = Mn;
-        float dloc = 0.f;
-        for (int s = d; s < nb; s += D) {
-            int64_t pr = pbase + (int64_t)(s0 + s) * RP + row;
-            float w = fast_exp2(a.part_ml[pr * 2] - Mu);
-            wgt[s] = w;
-            dloc += w * a.part_ml[pr * 2 + 1];
-        }
+        float w = fast_exp2(ms - Mu), dl = w * ls;     // threads >= nb: w = 0
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) dloc += __shfl_xor(dloc, o);
+        for (int off = 16; off > 0; off >>= 1) dl += __shfl_xor(dl, off);
+        if (d < SB) wgt[d] = w;
+        if (d == 0) red[1][0] = dl;
         __syncthreads();
-        if ((d & 63) == 0) red[d >> 6] = dloc;
-        __syncthreads();
-        for (int w = 0; w < D / 64; ++w) den += red[w];
-        const float* po = a.part_o + (pbase + (int64_t)s0 * RP + row) * D + d;
-        float acc4[4] = {0.f, 0.f, 0.f, 0.f};
-        int s = 0;
-        for (; s + 4 <= nb; s += 4) {
+        den = den * resc + red[1][0];
+        float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc4[j] += wgt[s + j] * po[(int64_t)(s + j) * RP * D];
+        for (int j = 0; j < SB; j += 2) {
+            acc0 = fmaf(wgt[j], o[j], acc0);
+            acc1 = fmaf(wgt[j + 1], o[j + 1], acc1);
         }
-        for (; s < nb; ++s) acc4[0] += wgt[s] * po[(int64_t)s * RP * D];
-        num += (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
+        num = num * resc + (acc0 + acc1);
+        __syncthreads();                               // wgt/red are rewritten by the next block
     }
     float o = den > 0.f ? num / den : 0.f;
     __bf16 ob = (__bf16)o;
@@ -536,7 +542,7 @@ hipError_t launch_split(const AttnLaunch& a, hipStream_t stream)
         if (e != hipSuccess) return e;
         configured[dev] = true;
     }
-    dim3 grid(a.nsplit, a.Hkv, a.B), block(kWaves * 64);
+    dim3 grid(a.Hkv, a.nsplit, a.B), block(kWaves * 64);
     hipLaunchKernelGGL(fn, grid, block, lds, stream, a);
     return hipGetLastError();
 }
