@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--chunk-tokens", type=int, default=0, help="KV split size override (0 = library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers of attention the oracle is timed on")
+    ap.add_argument("--kv-layout", choices=["head-major", "token-major"], default="head-major",
+                    help="KV cache memory order: [B,Hkv,L,d] (default, the layout the library prefers) or "
+                         "[B,L,Hkv,d]; paged: [pages,Hkv,page,d] or [pages,page,Hkv,d]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -81,16 +84,25 @@ def main():
     ctx_lens = torch.from_numpy(seqs.ctx_lens).to(dev)
     gammas = torch.from_numpy(seqs.gammas).to(dev)
     page_table = torch.from_numpy(seqs.page_table).to(dev) if cfg.paged else None
+    # logical shape is always [B or pages, tokens, Hkv, d]; the memory order is the layout's
     kv_shape = (seqs.n_pages, cfg.page_size, Hkv, d) if cfg.paged else (B, seqs.max_ctx, Hkv, d)
+    head_major = args.kv_layout == "head-major"
+
+    def kv_randn(g):
+        if head_major:
+            t = torch.randn((kv_shape[0], Hkv, kv_shape[1], d), dtype=torch.bfloat16, device=dev, generator=g)
+            return t.permute(0, 2, 1, 3)
+        return torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g)
+
     ks, vs, qs = [], [], []
     for layer in range(layers):
         g = torch.Generator(device=dev)
         g.manual_seed(1000 * wl.SEED_QKV + layer)
-        k = torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g)
+        k = kv_randn(g)
         if cfg.k_scale != 1.0:
             k.mul_(cfg.k_scale)
         ks.append(k)
-        vs.append(torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g))
+        vs.append(kv_randn(g))
         qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
     outs = [torch.empty_like(qs[0]) for _ in range(2)]
     g = torch.Generator(device=dev)
@@ -179,7 +191,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "ctx_tokens": tokens, "gamma": gmax, "vocab": V, "eta": cfg.eta,
-                   "kv_layout": "paged16" if cfg.paged else "[B,L,Hkv,d]", "chunk_tokens": chunk,
+                   "kv_layout": (("[pages,Hkv,16,d]" if head_major else "[pages,16,Hkv,d]") if cfg.paged
+                                 else ("[B,Hkv,L,d]" if head_major else "[B,L,Hkv,d]")), "chunk_tokens": chunk,
                    "kv_bytes_per_step": kv_bytes_step},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBPS, 4),
         "breakdown_us": {"attention_all_layers": round(attn_ms * 1e3, 1),

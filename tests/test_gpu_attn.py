@@ -181,6 +181,52 @@ def test_llama8b_128k_layers_full_size():
         check(cfg, inp, what=f"{cfg.name}[layer {layer}]")
 
 
+def test_llama8b_128k_head_major_full_size():
+    """Config 3 shape with the cache in [B, Hkv, L, d] memory order (the layout the benchmark
+    times by default): same data, strides only; every output element against the oracle."""
+    cfg = wl.CONFIGS["llama8b_128k_step"]
+    inp = wl.gen_attn_inputs(cfg, layer=1)
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    kh = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    vh = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    del k, v
+    ctx = torch.from_numpy(inp.seqs.ctx_lens).cuda()
+    out = gu.rapid().rapid_verify_attn(q, kh, vh, ctx, softmax_scale=cfg.softmax_scale)
+    torch.cuda.synchronize()
+    import oracle
+    bs, ts, hs, ps = wl.kv_strides(cfg, inp.seqs)
+    ref = oracle.verify_attn(inp.q, inp.k, inp.v, inp.seqs.ctx_lens, oracle.KVLayout(bs, ts, hs),
+                             Hkv=cfg.n_kv_heads, scale=cfg.softmax_scale, gammas=inp.seqs.gammas)
+    e_abs, e_rel = gu.assert_attn_close(gu.bf16_to_host(out), ref, "head-major 128k")
+    print(f"[head-major 128k] max_abs={e_abs:.3e} max_rel={e_rel:.3e}")
+
+
+def test_ragged_paged_full_size():
+    """Config 4 at its real size: 8 sequences of 16K-128K tokens, gamma in {4,6,8}, 16-token
+    pages with a seeded random page table; every output element against the oracle."""
+    cfg = wl.CONFIGS["ragged_paged"]
+    inp = wl.gen_attn_inputs(cfg)
+    assert inp.seqs.ctx_lens.min() >= 16384 and inp.seqs.ctx_lens.max() <= 131072
+    check(cfg, inp, what=f"{cfg.name} sum_ctx={int(inp.seqs.ctx_lens.sum())}")
+
+
+def test_ragged_paged_head_major_pages():
+    """Pages stored [n_pages, Hkv, 16, d] (each (page, head) 4 KiB contiguous), small sizes."""
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], batch=4, ctx=(500, 5000), name="paged_head_major")
+    inp = wl.gen_attn_inputs(cfg)
+    s = inp.seqs
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    kh = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    vh = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    args = dict(gammas=torch.from_numpy(s.gammas).cuda(), page_table=torch.from_numpy(s.page_table).cuda(),
+                max_ctx=s.max_ctx, softmax_scale=cfg.softmax_scale, chunk_tokens=512)
+    ctx = torch.from_numpy(s.ctx_lens).cuda()
+    a = gu.rapid().rapid_verify_attn(q, k, v, ctx, **args).clone()
+    b = gu.rapid().rapid_verify_attn(q, kh, vh, ctx, **args)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 def test_llama70b_128k_layer_full_size():
     """Config 5 shape (64 query heads, group 8 -> 72 packed rows), one layer."""
     cfg = wl.CONFIGS["llama70b_128k_step"]
