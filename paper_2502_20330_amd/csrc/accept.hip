@@ -12,7 +12,7 @@
 // an elementwise pass.  So the work is organised as reductions over the
 // vocabulary, chunked over many workgroups so the logits stream at HBM rate:
 //
-//   K1 row_stats      : per chunk (max z, sum exp((z - max)/T)) of every target and draft row
+//   K1 row_stats      : per chunk of 4096 entries (max z, sum exp((z - max)/T)) of every target and draft row
 //   K2 shifted_stats  : per chunk (max, sum exp) of d = (z - zmax)/T + eta (q - p)
 //   K3 decide         : one wave per row: combine chunks -> log-normalisers (double), accept
 //                       test in double at the drafted token -> pass/fail flag, ratio
@@ -31,7 +31,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kChunk = 1024;            // vocabulary entries per workgroup (4 per thread)
+constexpr int kVec = 4;                 // 128-bit loads per thread and chunk
+constexpr int kChunk = kThreads * 4 * kVec;   // vocabulary entries per workgroup (4096)
+constexpr int kSub = 256;                // entries per draw-weight partial sum (one wave x one 128-bit load)
+constexpr int kSubs = kChunk / kSub;     // partial sums per chunk
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
@@ -97,7 +100,7 @@ struct Ws {
     float2* st_d;     // [B][gmax][nch]
     float2* st_h;     // [B][gmax][nch]    (max d, sum exp(d - max d)), d relative to the target row max / T
     double* rows;     // [B][gmax+1][8]: zmax_t, lse_p, zmax_d, lse_q, lse_h, 1/S_h (= max p_hat), -, -
-    double* wsum;     // [B][nch][2]: sum of residual weights, sum of p (fallback)
+    double* wsum;     // [B][nch*kSubs][2]: per 256 entries, sum of residual weights and sum of p (fallback)
     int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
     int nch;
 };
@@ -113,7 +116,7 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
     w.st_d = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
     w.st_h = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
     w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 8 * sizeof(double));
-    w.wsum = reinterpret_cast<double*>(p); p += align256((size_t)B * w.nch * 2 * sizeof(double));
+    w.wsum = reinterpret_cast<double*>(p); p += align256((size_t)B * w.nch * kSubs * 2 * sizeof(double));
     w.flags = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * sizeof(int32_t));
     return w;
 }
@@ -130,12 +133,20 @@ __global__ void __launch_bounds__(kThreads) accept_row_stats(AcceptLaunch a, Ws 
     const float* row = is_t ? a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V
                             : a.zd + ((int64_t)b * a.gmax + k) * a.V;
     const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15) == 0);
-    floatx4 x = load4(row, ch * kChunk + threadIdx.x * 4, a.V, vec);
-    float m = block_max(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), sh);
+    floatx4 x[kVec];
+    float m = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) {
+        x[v] = load4(row, ch * kChunk + (v * kThreads + threadIdx.x) * 4, a.V, vec);
+        m = fmaxf(m, fmaxf(fmaxf(x[v][0], x[v][1]), fmaxf(x[v][2], x[v][3])));
+    }
+    m = block_max(m, sh);
     float s = 0.f;
     if (m > -INFINITY) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s += fexp((x[j] - m) * a.inv_T);
+        for (int v = 0; v < kVec; ++v)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += fexp((x[v][j] - m) * a.inv_T);
     }
     s = block_sum(s, sh);
     if (threadIdx.x == 0) {
@@ -162,38 +173,76 @@ __device__ __forceinline__ void combine_row(const float2* st, int nch, double in
 }
 
 // ---------------------------------------------------------------- K2
+// Row statistics of the target and the draft row, combined in fp32 by every workgroup
+// (enough for the elementwise pass; the decisions later use the fp64 combine of K3).
+__device__ __forceinline__ void combine_pair_f32(const float2* st_t, const float2* st_d, int nch, float inv_T,
+                                                 float* sh, float& Mt, float& lnSt, float& Md, float& lnSd)
+{
+    float mt = -INFINITY, md = -INFINITY;
+    for (int i = threadIdx.x; i < nch; i += kThreads) {
+        mt = fmaxf(mt, st_t[i].x);
+        md = fmaxf(md, st_d[i].x);
+    }
+    mt = wave_max(mt);
+    md = wave_max(md);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = mt; sh[4 + (threadIdx.x >> 6)] = md; }
+    __syncthreads();
+    Mt = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+    Md = fmaxf(fmaxf(sh[4], sh[5]), fmaxf(sh[6], sh[7]));
+    float st = 0.f, sd = 0.f;
+    for (int i = threadIdx.x; i < nch; i += kThreads) {
+        float2 t = st_t[i], d = st_d[i];
+        if (t.y > 0.f) st += t.y * fexp((t.x - Mt) * inv_T);
+        if (d.y > 0.f) sd += d.y * fexp((d.x - Md) * inv_T);
+    }
+    st = wave_sum(st);
+    sd = wave_sum(sd);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = st; sh[4 + (threadIdx.x >> 6)] = sd; }
+    __syncthreads();
+    lnSt = __logf((sh[0] + sh[1]) + (sh[2] + sh[3]));
+    lnSd = __logf((sh[4] + sh[5]) + (sh[6] + sh[7]));
+}
+
 __global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a, Ws ws)
 {
     __shared__ float sh[8];
-    __shared__ double shd[8];
     const int ch = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
     if (k >= g) return;
     const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
     const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
     const bool vec = ((reinterpret_cast<uintptr_t>(zt) & 15) == 0) && ((reinterpret_cast<uintptr_t>(zd) & 15) == 0);
-    const int i0 = ch * kChunk + threadIdx.x * 4;
-    floatx4 x = load4(zt, i0, a.V, vec), y = load4(zd, i0, a.V, vec);   // in flight while the row statistics combine
-    double Mt, St, Md, Sd;
-    combine_row(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Mt, St);
-    combine_row(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, shd, Md, Sd);
-    const float zmax_t = (float)Mt, zmax_d = (float)Md;       // exact: they are float values
-    const float lnS_t = (float)log(St), lnS_d = (float)log(Sd);
-    float d[4];
+    floatx4 x[kVec], y[kVec];                     // in flight while the row statistics combine
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) {
+        const int i0 = ch * kChunk + (v * kThreads + threadIdx.x) * 4;
+        x[v] = load4(zt, i0, a.V, vec);
+        y[v] = load4(zd, i0, a.V, vec);
+    }
+    float zmax_t, lnS_t, zmax_d, lnS_d;
+    combine_pair_f32(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch,
+                     ws.nch, a.inv_T, sh, zmax_t, lnS_t, zmax_d, lnS_d);
     float m = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float at = (x[j] - zmax_t) * a.inv_T;              // z/T relative to the row max
-        float ad = (y[j] - zmax_d) * a.inv_T;
-        float p = fexp(at - lnS_t), q = fexp(ad - lnS_d);
-        d[j] = (i0 + j < a.V) ? fmaf(a.eta, q - p, at) : -INFINITY;
-        m = fmaxf(m, d[j]);
-    }
+    for (int v = 0; v < kVec; ++v)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float at = (x[v][j] - zmax_t) * a.inv_T;          // z/T relative to the row max
+            float ad = (y[v][j] - zmax_d) * a.inv_T;
+            float p = fexp(at - lnS_t), q = fexp(ad - lnS_d);
+            // entries past V were loaded as -inf: at = -inf, p = q = 0 -> d = -inf
+            x[v][j] = fmaf(a.eta, q - p, at);
+            m = fmaxf(m, x[v][j]);
+        }
     m = block_max(m, sh);
     float s = 0.f;
     if (m > -INFINITY) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s += fexp(d[j] - m);
+        for (int v = 0; v < kVec; ++v)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += fexp(x[v][j] - m);
     }
     s = block_sum(s, sh);
     if (threadIdx.x == 0) ws.st_h[((int64_t)b * a.gmax + k) * ws.nch + ch] = make_float2(m, s);
@@ -309,7 +358,6 @@ __device__ __forceinline__ void weights(const RowCtx& c, int v, double& w, doubl
 // ---------------------------------------------------------------- K4
 __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a, Ws ws)
 {
-    __shared__ double shd[8];
     const int ch = blockIdx.x, b = blockIdx.y;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
     const int n = first_reject(ws, b, a.gmax, g);
@@ -319,22 +367,28 @@ __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a,
         if (k == 0) a.n_accepted[b] = n;
     }
     RowCtx c = make_row_ctx(a, ws, b, n, g);
-    double sw = 0.0, sp = 0.0;
-    const int i0 = ch * kChunk + threadIdx.x * 4;
+    // one partial sum per wave and 128-bit load: a run of 256 consecutive entries
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (i0 + j < a.V) {
-            double w, p;
-            weights(c, i0 + j, w, p);
-            sw += w;
-            sp += p;
+    for (int v = 0; v < kVec; ++v) {
+        const int i0 = ch * kChunk + (v * kThreads + threadIdx.x) * 4;
+        double sw = 0.0, sp = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < a.V) {
+                double w, p;
+                weights(c, i0 + j, w, p);
+                sw += w;
+                sp += p;
+            }
         }
-    }
-    sw = block_sum(sw, shd);
-    sp = block_sum(sp, shd);
-    if (threadIdx.x == 0) {
-        ws.wsum[((int64_t)b * ws.nch + ch) * 2 + 0] = sw;
-        ws.wsum[((int64_t)b * ws.nch + ch) * 2 + 1] = sp;
+        sw = wave_sum(sw);
+        sp = wave_sum(sp);
+        if (lane == 0) {
+            const int64_t sub = ((int64_t)b * ws.nch + ch) * kSubs + v * (kThreads / 64) + wave;
+            ws.wsum[sub * 2 + 0] = sw;
+            ws.wsum[sub * 2 + 1] = sp;
+        }
     }
 }
 
@@ -377,12 +431,13 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
     const int g = a.gammas ? a.gammas[b] : a.gmax;
     const int n = first_reject(ws, b, a.gmax, g);
     RowCtx c = make_row_ctx(a, ws, b, n, g);
-    const double* cs = ws.wsum + (int64_t)b * ws.nch * 2;
+    const int nsub = ws.nch * kSubs;             // partial sums of 256 entries, in vocabulary order
+    const double* cs = ws.wsum + (int64_t)b * nsub * 2;
     if (tid == 0) { pick_chunk = -1; last_chunk = 0; pick_lo = 0x7fffffff; pick_hi = -1; }
 
     // every thread owns `per` consecutive chunks
-    const int per = (ws.nch + kThreads - 1) / kThreads;
-    const int cbeg = min(tid * per, ws.nch), cend = min(cbeg + per, ws.nch);
+    const int per = (nsub + kThreads - 1) / kThreads;
+    const int cbeg = min(tid * per, nsub), cend = min(cbeg + per, nsub);
     double tw = 0.0, tp = 0.0;
     for (int i = cbeg; i < cend; ++i) { tw += cs[i * 2]; tp += cs[i * 2 + 1]; }
     double Wres, Wp, in_w, in_p;
@@ -418,10 +473,11 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
         }
         __syncthreads();
     }
-    const int i0 = pick_chunk * kChunk + tid * 4;
-    double w[4], local = 0.0;
+    constexpr int kPer = kSub / kThreads;           // entries per thread inside the chosen run
+    const int i0 = pick_chunk * kSub + tid * kPer;
+    double w[kPer], local = 0.0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kPer; ++j) {
         w[j] = 0.0;
         if (i0 + j < a.V) {
             double ww, pp;
@@ -432,15 +488,18 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
     }
     double chunk_total, local_incl;
     double run = chunk_base + block_scan(local, shd, local_incl, chunk_total);
+    int my_lo = 0x7fffffff, my_hi = -1;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kPer; ++j) {
         double nxt = run + w[j];
         if (w[j] > 0.0) {
-            atomicMax(&pick_hi, i0 + j);
-            if (nxt > t) atomicMin(&pick_lo, i0 + j);
+            my_hi = i0 + j;
+            if (nxt > t) my_lo = min(my_lo, i0 + j);
         }
         run = nxt;
     }
+    if (my_hi >= 0) atomicMax(&pick_hi, my_hi);
+    if (my_lo != 0x7fffffff) atomicMin(&pick_lo, my_lo);
     __syncthreads();
     if (tid == 0) {
         int tok = pick_lo != 0x7fffffff ? pick_lo : pick_hi;   // pick_hi: rounding at the chunk's end
