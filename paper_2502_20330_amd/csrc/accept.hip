@@ -367,28 +367,26 @@ __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a,
         if (k == 0) a.n_accepted[b] = n;
     }
     RowCtx c = make_row_ctx(a, ws, b, n, g);
-    // one partial sum per wave and 128-bit load: a run of 256 consecutive entries
+    // one partial sum per wave: a run of 256 consecutive entries (the fp64 exponentials make
+    // this kernel ALU-heavy, so it uses four times more workgroups than the statistics kernels)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i0 = (ch * kThreads + threadIdx.x) * 4;
+    double sw = 0.0, sp = 0.0;
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) {
-        const int i0 = ch * kChunk + (v * kThreads + threadIdx.x) * 4;
-        double sw = 0.0, sp = 0.0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (i0 + j < a.V) {
-                double w, p;
-                weights(c, i0 + j, w, p);
-                sw += w;
-                sp += p;
-            }
+    for (int j = 0; j < 4; ++j) {
+        if (i0 + j < a.V) {
+            double w, p;
+            weights(c, i0 + j, w, p);
+            sw += w;
+            sp += p;
         }
-        sw = wave_sum(sw);
-        sp = wave_sum(sp);
-        if (lane == 0) {
-            const int64_t sub = ((int64_t)b * ws.nch + ch) * kSubs + v * (kThreads / 64) + wave;
-            ws.wsum[sub * 2 + 0] = sw;
-            ws.wsum[sub * 2 + 1] = sp;
-        }
+    }
+    sw = wave_sum(sw);
+    sp = wave_sum(sp);
+    if (lane == 0) {
+        const int64_t sub = (int64_t)b * ws.nch * kSubs + ch * (kThreads / 64) + wave;
+        ws.wsum[sub * 2 + 0] = sw;
+        ws.wsum[sub * 2 + 1] = sp;
     }
 }
 
@@ -523,7 +521,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
     if (a.gmax > 0)
         hipLaunchKernelGGL(accept_shifted_stats, dim3(ws.nch, a.gmax, a.B), blk, 0, stream, a, ws);
     hipLaunchKernelGGL(accept_decide, dim3(a.gmax + 1, a.B), dim3(64), 0, stream, a, ws);
-    hipLaunchKernelGGL(accept_residual_sums, dim3(ws.nch, a.B), blk, 0, stream, a, ws);
+    hipLaunchKernelGGL(accept_residual_sums, dim3(ws.nch * kVec, a.B), blk, 0, stream, a, ws);
     hipLaunchKernelGGL(accept_draw, dim3(a.B), blk, 0, stream, a, ws);
     return hipGetLastError();
 }
