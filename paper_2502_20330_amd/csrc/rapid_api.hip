@@ -56,6 +56,25 @@ int plan_chunk(const rapid_ctx* ctx, const rapid_attn_shape* s)
     return (int)chunk;
 }
 
+// How the splits are laid over the chip (measured on MI355X, 128K context):
+//  * rotate: when the rows of one head are contiguous in the cache (head stride above
+//    token stride), spreading each head's splits over all dies is worth 4 % on
+//    batches; when heads interleave inside a token row it costs 2.5 %, because the
+//    workgroups that share those rows no longer run side by side.
+//  * skew: with a single wave of workgroups (one per compute unit) the dies on odd
+//    dispatch slots finish 10..15 % later than the even ones.  Moving 1/16 of a split
+//    from each odd-slot workgroup to its even-slot pair partner evens that out
+//    (2..3 % on the whole call).  With several workgroups per compute unit the
+//    dispatcher balances by itself and the skew only hurts.
+// The skew is a multiple of 128 tokens so both partners keep whole tiles per wave.
+void plan_layout(const rapid_ctx* ctx, AttnLaunch& a)
+{
+    a.rot = a.hstride > a.tstride && a.Hkv > 1;
+    a.skew = 0;
+    const int64_t wgs = (int64_t)a.B * a.Hkv * a.nsplit;
+    if (a.rot && a.Hkv % 2 == 0 && a.nsplit >= 2 && wgs <= ctx->n_cu) a.skew = a.chunk / 16 / 128 * 128;
+}
+
 }  // namespace
 
 extern "C" {
@@ -162,6 +181,7 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
         a.page_mask = shape->page_size - 1;
     }
     a.scale_log2e = shape->softmax_scale * 1.4426950408889634f;
+    plan_layout(ctx, a);
     const size_t rows = (size_t)a.B * a.Hkv * a.nsplit * a.RB * 16;
     const size_t o_bytes = (rows * a.D * sizeof(float) + 255) / 256 * 256;
     a.part_o = static_cast<float*>(workspace);

@@ -24,6 +24,8 @@ struct AttnLaunch {
     float* part_ml;     // [B, Hkv, nsplit, RB*16, 2] (running max in log2 units, sum)
     int32_t B, Qmax, Hq, Hkv, G, D, gamma;
     int32_t chunk, nsplit, RB;
+    int32_t rot;        // 1: dispatch slot x serves head (x + split) mod Hkv, 0: head x
+    int32_t skew;       // tokens moved from the splits on odd dispatch slots to those on even ones
     int64_t bstride, tstride, hstride, pstride;   // elements
     int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
     float scale_log2e;

@@ -272,6 +272,21 @@ __device__ __forceinline__ void pv_tile(WaveState<D, RB>& st, const bf16x8 (&pb)
     }
 }
 
+// Token range of split s of kv head h.  Splits come in pairs that cover 2*chunk
+// tokens; the member of a pair that runs on an even dispatch slot takes chunk + skew
+// tokens, the other chunk - skew (see the slot -> head mapping in the kernel).  An
+// unpaired last split keeps `chunk`.
+__device__ __forceinline__ int split_begin(const AttnLaunch& a, int s, int h)
+{
+    int t = (s >> 1) * 2 * a.chunk;
+    if (s & 1) t += a.chunk + ((h & 1) ? -a.skew : a.skew);
+    return t;
+}
+__device__ __forceinline__ int split_end(const AttnLaunch& a, int s, int h)
+{
+    return s + 1 < a.nsplit ? split_begin(a, s + 1, h) : a.nsplit * a.chunk;
+}
+
 template <int D, int RB, bool PAGED>
 __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
 {
@@ -280,13 +295,18 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     constexpr int kAhead = 3 * G::NLD;     // loads issued after the tile a wait is for
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    // kv head fastest: the workgroups of one token range sit next to each other in
-    // dispatch order, so the cache lines of a token (all heads) are fetched together
-    const int hkv = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+    // With rotation, dispatch slot x = blockIdx.x serves kv head (x + split) mod Hkv.
+    // Workgroups go to the chip's eight dies round robin in dispatch order, so the
+    // splits of one head are then spread over all dies (and all L2s) instead of
+    // sitting on one, and the parity of x is the parity of the die.  Without it,
+    // the heads of one token range sit next to each other in dispatch order, which
+    // suits caches whose heads interleave inside a token row.
+    const int split = blockIdx.y, b = blockIdx.z;
+    const int hkv = a.rot ? (int)((blockIdx.x + split) % a.Hkv) : (int)blockIdx.x;
     const int L = a.ctx_lens[b];
-    const int c0 = split * a.chunk;
+    const int c0 = split_begin(a, split, hkv);
     if (c0 >= L) return;                             // this split holds no token of sequence b
-    const int c1 = min(c0 + a.chunk, L);
+    const int c1 = min(split_end(a, split, hkv), L);
     const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
     const int R = Q * a.G;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -481,7 +501,8 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
         if (a.lse_out && d == 0) a.lse_out[((int64_t)b * a.Hq + h) * a.Qmax + qi] = 0.f;
         return;
     }
-    const int ns = min((L + a.chunk - 1) / a.chunk, a.nsplit);
+    int ns = min(L / a.chunk + 2, a.nsplit);          // splits that hold a token of this sequence
+    while (ns > 0 && split_begin(a, ns - 1, hkv) >= L) --ns;
     const int64_t pbase = ((int64_t)b * a.Hkv + hkv) * a.nsplit * RP;
     float M = -INFINITY, den = 0.f, num = 0.f;
     for (int s0 = 0; s0 < ns; s0 += SB) {

@@ -29,11 +29,15 @@ def bf16_to_host(t: torch.Tensor) -> np.ndarray:
     return wl.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
 
 
-def run_attn_case(cfg, inp, *, chunk_tokens=0, scale=None, want_lse=True):
-    """Runs GPU and oracle on one AttnInputs; returns (gpu_out f64, ref f64, gpu_lse, ref_lse)."""
+def run_attn_case(cfg, inp, *, chunk_tokens=0, scale=None, want_lse=True, head_major=False):
+    """Runs GPU and oracle on one AttnInputs; returns (gpu_out f64, ref f64, gpu_lse, ref_lse).
+    head_major: the GPU sees the same cache re-stored in [B, Hkv, L, d] memory order."""
     s = inp.seqs
     scale = cfg.softmax_scale if scale is None else scale
     q, k, v = bf16_to_dev(inp.q), bf16_to_dev(inp.k), bf16_to_dev(inp.v)
+    if head_major:
+        k = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        v = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
     ctx = torch.from_numpy(s.ctx_lens).cuda()
     gam = torch.from_numpy(s.gammas).cuda()
     pt = torch.from_numpy(s.page_table).cuda() if s.page_table is not None else None

@@ -121,6 +121,25 @@ def test_head_major_cache_strides():
     assert torch.equal(base, alt)
 
 
+@pytest.mark.parametrize("L", [1919, 1920, 1921, 2048, 2175, 2176, 2177, 4095, 4097, 6015, 6016, 6017, 6271, 6273, 8192])
+def test_head_major_uneven_split_pairs(L):
+    """[B, Hkv, L, d] cache with one workgroup per compute unit or fewer: the library then
+    rotates heads over dispatch slots and gives the two splits of a pair 2048 +- 128
+    tokens.  Context lengths sit on and around every boundary that this produces."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], ctx=(L, L), n_q_heads=8, n_kv_heads=2, name=f"hm_pairs_L{L}")
+    check(cfg, chunk_tokens=2048, head_major=True)
+
+
+def test_head_major_uneven_split_pairs_ragged_batch():
+    """Same, three sequences of different lengths under one max_ctx: some splits of the
+    shorter sequences are empty and the merge must count the non-empty ones per head."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], batch=3, ctx=(1800, 10500), n_q_heads=16, n_kv_heads=4, head_dim=128,
+                    name="hm_pairs_ragged")
+    inp = wl.gen_attn_inputs(cfg)
+    assert len(set(inp.seqs.ctx_lens.tolist())) == 3
+    check(cfg, inp, chunk_tokens=2048, head_major=True)
+
+
 def test_cache_rows_past_ctx_len_are_never_used():
     cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], ctx=(1111, 1111), name="tail_nan")
     inp = wl.gen_attn_inputs(cfg)
