@@ -197,7 +197,7 @@ def main():
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBPS, 4),
         "breakdown_us": {"attention_all_layers": round(attn_ms * 1e3, 1),
                          "attention_per_layer": round(attn_launch_ms * 1e3, 2), "accept": round(acc_ms * 1e3, 2)},
-        "roofline": {"bound": "hbm", "kernel": "verify_attn (split-KV + merge, per layer)",
+        "roofline": {"bound": "hbm", "kernel": "rapid_verify_attn (verify_attn_split + verify_attn_merge, one call = one layer)",
                      "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": kv_bytes_layer,
