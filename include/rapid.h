@@ -153,6 +153,22 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                  int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid, not part of the method: reads `bytes` bytes of device memory at
+ * `buf` once, with the load path of rapid_verify_attn (HBM -> LDS, streaming hint)
+ * and no arithmetic, so that a benchmark can time the read bandwidth this device
+ * actually delivers and quote kernel rates against it as well as against the
+ * published peak.
+ *
+ *   buf    device memory, 16-byte aligned, not written
+ *   bytes  a multiple of 16384, at least 16384 and below 2^46
+ *   sink   4 bytes of device memory or NULL; written only if the XOR of the words
+ *          the kernel inspects equals one particular constant (this keeps the loads
+ *          observable), so treat its content as unspecified
+ * Returns RAPID_EINVAL / RAPID_EALIGN on bad arguments, RAPID_EHIP on launch failure.
+ */
+int rapid_hbm_read_probe(rapid_ctx* ctx, const void* buf, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

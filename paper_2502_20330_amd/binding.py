@@ -16,9 +16,10 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "librapid.so")
 
 RAPID_OK = 0
+RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP = -1, -2, -3, -4, -5
 EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
-           "rapid_accept_workspace_bytes", "rapid_accept"]
+           "rapid_accept_workspace_bytes", "rapid_accept", "rapid_hbm_read_probe"]
 
 
 class RapidError(RuntimeError):
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
                                  ctypes.c_float, ctypes.c_float, ctypes.c_float, f32p, i32p, i32p, f32p,
                                  vp, ctypes.c_size_t, vp]
     lib.rapid_accept.restype = ctypes.c_int
+    lib.rapid_hbm_read_probe.argtypes = [ctypes.c_void_p, vp, ctypes.c_size_t, vp, vp]
+    lib.rapid_hbm_read_probe.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -104,6 +107,7 @@ class Rapid:
         torch.cuda.set_device(self.device)
         _check(self.lib, self.lib.rapid_create(ctypes.byref(self._ctx), device))
         self._ws: Optional[torch.Tensor] = None
+        self._sink: Optional[torch.Tensor] = None
 
     def close(self):
         if self._ctx:
@@ -203,9 +207,20 @@ class Rapid:
         _check(self.lib, rc, self._ctx)
         return n_acc, toks, ratio
 
+    # ------------------------------------------------------------------ measurement aid
+    def rapid_hbm_read_probe(self, buf: torch.Tensor, nbytes: Optional[int] = None):
+        """Streams the first `nbytes` bytes (default: all, rounded down to 16 KiB) of a dense tensor's
+        memory through the attention kernel's load path; for timing only."""
+        total = buf.numel() * buf.element_size()
+        nbytes = (total if nbytes is None else nbytes) // 16384 * 16384
+        if self._sink is None:
+            self._sink = torch.zeros(1, dtype=torch.int32, device=self.device)
+        _check(self.lib, self.lib.rapid_hbm_read_probe(self._ctx, _dptr(buf), nbytes, _dptr(self._sink),
+                                                       _stream_ptr(self.device)), self._ctx)
+        return nbytes
+
 
 _default: dict = {}
-
 
 def _get(device: int = 0) -> Rapid:
     if device not in _default:

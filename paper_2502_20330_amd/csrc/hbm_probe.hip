@@ -1,0 +1,68 @@
+// Streaming-read probe: what read bandwidth the device delivers when nothing else
+// limits the kernel.  Not part of the method; it gives the benchmark a measured
+// ceiling to set next to the published 8 TB/s.  It moves memory exactly the way the
+// attention kernel does (HBM -> LDS, 1 KiB per instruction, streaming hint, every
+// wave on its own contiguous range, a two-slot ring of 16 KiB blocks per wave) and
+// does no arithmetic on it.
+#include "rapid_internal.h"
+
+namespace {
+
+constexpr int kBlock = 16384;      // bytes per ring slot
+constexpr int kWaves = 4;
+
+__global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, int64_t nblock, uint32_t* sink)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t w = (int64_t)blockIdx.x * kWaves + wave, nw = (int64_t)gridDim.x * kWaves;
+    const int64_t b0 = nblock * w / nw, b1 = nblock * (w + 1) / nw;   // this wave's blocks
+    const int n = (int)(b1 - b0);
+    if (n <= 0) return;
+    const char* base = buf + b0 * kBlock;
+    const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * 2 * kBlock;
+    auto issue = [&](int t) {
+        const char* bp = base + (int64_t)(t < n ? t : n - 1) * kBlock;   // clamped: always inside the range
+#pragma unroll
+        for (int e = 0; e < kBlock / 1024; ++e) {
+            const uint32_t off = e * 1024 + lane * 16;
+            const uint32_t dst = ring + (t & 1) * kBlock + e * 1024;
+            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                         :
+                         : "v"(off), "s"(bp), "s"(dst)
+                         : "memory", "m0");
+        }
+    };
+    issue(0);
+    uint32_t acc = 0;
+    for (int t = 0; t < n; ++t) {
+        issue(t + 1);
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");              // block t has landed
+        acc ^= *reinterpret_cast<const uint32_t*>(smem + wave * 2 * kBlock + (t & 1) * kBlock + lane * 4);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (acc == 0x9E3779B9u && sink) *sink = acc;                       // keeps the reads alive
+}
+
+}  // namespace
+
+hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream)
+{
+    constexpr int lds = kWaves * 2 * kBlock;
+    static bool configured[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 64 && !configured[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(hbm_read_stream),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        configured[dev] = true;
+    }
+    const int64_t nblock = (int64_t)(bytes / kBlock);
+    hipLaunchKernelGGL(hbm_read_stream, dim3(ctx->n_cu), dim3(kWaves * 64), lds, stream,
+                       static_cast<const char*>(buf), nblock, sink);
+    return hipGetLastError();
+}

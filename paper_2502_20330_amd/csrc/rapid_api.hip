@@ -236,4 +236,14 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     return RAPID_OK;
 }
 
+int rapid_hbm_read_probe(rapid_ctx* ctx, const void* buf, size_t bytes, void* sink, void* stream)
+{
+    if (!ctx || !buf) return RAPID_EINVAL;
+    if (bytes < 16384 || bytes % 16384 || bytes >= ((size_t)1 << 46)) return RAPID_EINVAL;
+    if (!aligned(buf, 16) || (sink && !aligned(sink, 4))) return RAPID_EALIGN;
+    hipError_t e = launch_hbm_read_probe(ctx, buf, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
 }  // extern "C"

@@ -50,3 +50,6 @@ struct AcceptLaunch {
 };
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int gmax, int V);
+
+// ---- streaming-read probe (hbm_probe.hip)
+hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream);

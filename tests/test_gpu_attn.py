@@ -250,3 +250,19 @@ def test_llama70b_128k_layer_full_size():
     """Config 5 shape (64 query heads, group 8 -> 72 packed rows), one layer."""
     cfg = wl.CONFIGS["llama70b_128k_step"]
     check(cfg, wl.gen_attn_inputs(cfg, layer=0), what=f"{cfg.name}[layer 0]")
+
+
+def test_hbm_read_probe_runs_and_checks_arguments():
+    """The measurement aid streams a buffer without touching it and rejects sizes it cannot split."""
+    from paper_2502_20330_amd import binding
+    r = gu.rapid()
+    buf = torch.arange(3 * 16384 * 50 + 100, dtype=torch.uint8, device="cuda")
+    before = buf.clone()
+    n = r.rapid_hbm_read_probe(buf)
+    torch.cuda.synchronize()
+    assert n == 3 * 16384 * 50 and torch.equal(buf, before)
+    assert r.rapid_hbm_read_probe(buf, 16384) == 16384           # fewer blocks than waves
+    torch.cuda.synchronize()
+    import ctypes
+    bad = r.lib.rapid_hbm_read_probe(r._ctx, ctypes.c_void_p(buf.data_ptr()), 1000, None, None)
+    assert bad == binding.RAPID_EINVAL
