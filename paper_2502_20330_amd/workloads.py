@@ -80,6 +80,13 @@ CONFIGS = {
     "llama70b_128k_step": VerifyConfig("llama70b_128k_step", 80, 1, 64, 8, 128, (131072, 131072),
                                        (8,), 128256, 0.5, 4.0, 1.0, k_scale=1.0 / math.sqrt(128),
                                        etas=(0.25, 0.5, 1.0)),
+    # next rows: the drafter's own decode step on the retrieved context (Sec. 2.2: the drafter works on
+    # the shortened context, one position per step): the same two calls at gamma = 0, where the accept
+    # call reduces to drawing the next token from softmax(z / T)
+    "drafter_decode_8k": VerifyConfig("drafter_decode_8k", 32, 1, 32, 8, 128, (8192, 8192), (0,), 128256,
+                                      0.0, 4.0, 1.0, k_scale=1.0 / math.sqrt(128)),
+    "drafter_decode_16k_b8": VerifyConfig("drafter_decode_16k_b8", 32, 8, 32, 8, 128, (4096, 16384), (0,), 128256,
+                                          0.0, 4.0, 1.0, k_scale=1.0 / math.sqrt(128)),
 }
 
 

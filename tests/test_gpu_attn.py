@@ -266,3 +266,16 @@ def test_hbm_read_probe_runs_and_checks_arguments():
     import ctypes
     bad = r.lib.rapid_hbm_read_probe(r._ctx, ctypes.c_void_p(buf.data_ptr()), 1000, None, None)
     assert bad == binding.RAPID_EINVAL
+
+
+@pytest.mark.parametrize("name", ["drafter_decode_8k", "drafter_decode_16k_b8"])
+def test_drafter_decode_step_full_size(name):
+    """The drafter's decode step on the retrieved context (Sec. 2.2): one query position per
+    sequence (gamma = 0, 4 packed rows per kv head), 8K tokens / a ragged batch of 4K-16K tokens,
+    two layers, in both cache orders; every output element against the oracle."""
+    cfg = wl.CONFIGS[name]
+    for layer in (0, cfg.layers - 1):
+        inp = wl.gen_attn_inputs(cfg, layer=layer)
+        assert int(inp.seqs.gammas.max()) == 0
+        check(cfg, inp, what=f"{name}[layer {layer}]")
+        check(cfg, inp, what=f"{name}[layer {layer}, head-major]", head_major=True)
