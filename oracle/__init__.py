@@ -44,6 +44,8 @@ def _load():
         lib.oracle_verify_attn.restype = ctypes.c_int
         lib.oracle_accept.restype = ctypes.c_int
         lib.oracle_distributions.restype = None
+        lib.oracle_lm_head.restype = ctypes.c_int
+        lib.oracle_chunk_stats.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -151,3 +153,35 @@ def distributions(z, zq, *, eta, temperature=1.0, tail_alpha=0.1):
                              _ptr(p, ctypes.c_double), _ptr(q, ctypes.c_double),
                              _ptr(ph, ctypes.c_double))
     return p, q, ph
+
+
+def lm_head(h_bits, w_bits):
+    """z = h W^T in float64 from bf16 bit patterns: h uint16 [rows, hidden], w uint16 [vocab, hidden]."""
+    lib = _load()
+    h = np.ascontiguousarray(h_bits, dtype=np.uint16)
+    w = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    rows, hidden = h.shape
+    vocab, hidden_w = w.shape
+    if hidden_w != hidden:
+        raise ValueError("hidden sizes differ")
+    z = np.empty((rows, vocab), dtype=np.float64)
+    rc = lib.oracle_lm_head(ctypes.c_int(rows), ctypes.c_int64(hidden), ctypes.c_int64(vocab),
+                            _ptr(h, ctypes.c_uint16), _ptr(w, ctypes.c_uint16), _ptr(z, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_lm_head: invalid argument (rc={rc})")
+    return z
+
+
+def chunk_stats(z, chunk: int, temperature: float = 1.0):
+    """Per block of `chunk` vocabulary entries: (max z, sum exp((z - max)/T)), float64 [rows, nch] each."""
+    lib = _load()
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    rows, vocab = z.shape
+    nch = (vocab + chunk - 1) // chunk
+    cmax = np.empty((rows, nch)); csum = np.empty((rows, nch))
+    rc = lib.oracle_chunk_stats(ctypes.c_int(rows), ctypes.c_int64(vocab), ctypes.c_int64(chunk),
+                                ctypes.c_double(temperature), _ptr(z, ctypes.c_double),
+                                _ptr(cmax, ctypes.c_double), _ptr(csum, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_chunk_stats: invalid argument (rc={rc})")
+    return cmax, csum

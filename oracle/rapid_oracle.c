@@ -7,7 +7,7 @@
  * header, table or helper with the GPU library; only tests, the smoke check
  * and the CPU-baseline leg of the benchmark may call it.
  *
- * Two functions:
+ * Functions:
  *
  *   oracle_verify_attn  -- the target model's attention for the gamma+1
  *       verification positions against the whole KV cache ("validated by the
@@ -29,6 +29,15 @@
  *         all accepted:    x ~ p of the next position    (Sec. 2.1 background)
  *       How a uniform number is turned into a token (inverse CDF in index
  *       order) is an interface convention of this build, not the paper's.
+ *
+ *   oracle_lm_head      -- what "LogitsOf" (Alg. 1) means for a decoder
+ *       language model: the logits of a position are its final hidden state
+ *       times the output embedding, z[r][v] = sum_k h[r][k] * W[v][k] (no
+ *       bias; the final normalisation is the caller's).  The paper does not
+ *       spell this out; it is the standard head of the models it uses.
+ *   oracle_chunk_stats  -- per block of `chunk` consecutive vocabulary entries,
+ *       max_v z and sum_v exp((z - max)/T): the pieces from which
+ *       softmax(z/T) of Alg. 1 is normalised.
  *
  * Pins: every function here is pinned by tests that do not call it to check
  * itself (dense torch attention on tiny inputs, closed forms, the eta = 0
@@ -306,6 +315,50 @@ int oracle_accept(int B, int gmax, int64_t V,
         }
         n_accepted[b] = n;
         free(z); free(zq); free(p); free(q); free(ph); free(w);
+    }
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ */
+/* Output head: z[r][v] = sum_k h[r][k] * W[v][k], bf16 inputs widened   */
+/* exactly, accumulated in double in index order.                        */
+/*   h bf16 [rows][hidden], w bf16 [vocab][hidden], z double [rows][vocab] */
+int oracle_lm_head(int rows, int64_t hidden, int64_t vocab,
+                   const uint16_t* h, const uint16_t* w, double* z)
+{
+    if (rows < 1 || hidden < 1 || vocab < 1 || !h || !w || !z) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < vocab; ++v) {
+        for (int r = 0; r < rows; ++r) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < hidden; ++k)
+                acc += bf16_to_double(h[(int64_t)r * hidden + k]) * bf16_to_double(w[v * hidden + k]);
+            z[(int64_t)r * vocab + v] = acc;
+        }
+    }
+    return 0;
+}
+
+/* Per block c of `chunk` consecutive entries of every row:               */
+/*   cmax[r][c] = max_v z[r][v],  csum[r][c] = sum_v exp((z[r][v] - cmax)/T) */
+/* (the last block may be short).                                         */
+int oracle_chunk_stats(int rows, int64_t vocab, int64_t chunk, double T,
+                       const double* z, double* cmax, double* csum)
+{
+    if (rows < 1 || vocab < 1 || chunk < 1 || !(T > 0.0) || !z || !cmax || !csum) return -1;
+    const int64_t nch = (vocab + chunk - 1) / chunk;
+    for (int r = 0; r < rows; ++r) {
+        for (int64_t c = 0; c < nch; ++c) {
+            const int64_t v0 = c * chunk, v1 = v0 + chunk < vocab ? v0 + chunk : vocab;
+            double m = -INFINITY;
+            for (int64_t v = v0; v < v1; ++v)
+                if (z[(int64_t)r * vocab + v] > m) m = z[(int64_t)r * vocab + v];
+            double s = 0.0;
+            for (int64_t v = v0; v < v1; ++v) s += exp((z[(int64_t)r * vocab + v] - m) / T);
+            cmax[r * nch + c] = m;
+            csum[r * nch + c] = s;
+        }
     }
     return 0;
 }
