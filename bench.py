@@ -14,6 +14,7 @@ from __future__ import annotations
 import argparse
 import ctypes
 import json
+import math
 import os
 import re
 import sys
@@ -38,6 +39,9 @@ def parse_args():
     ap.add_argument("--kv-layout", choices=["head-major", "token-major"], default="head-major",
                     help="KV cache memory order: [B,Hkv,L,d] (default, the layout the library prefers) or "
                          "[B,L,Hkv,d]; paged: [pages,Hkv,page,d] or [pages,page,Hkv,d]")
+    ap.add_argument("--with-lm-head", action="store_true",
+                    help="also run the target's output head (hidden x vocab bf16 weights) inside every step and feed "
+                         "its logits and row statistics to the accept pass (batch 1 workloads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -124,6 +128,24 @@ def main():
     draft_tokens = torch.argmax(zd / cfg.temperature + gumbel, dim=-1).to(torch.int32)
     del gumbel
     uniforms = torch.rand((B, gmax + 1), device=dev, generator=g)
+    head = None
+    if args.with_lm_head:
+        if B * (gmax + 1) > 16:
+            print("bench.py: --with-lm-head handles at most 16 verification rows", file=sys.stderr)
+            sys.exit(2)
+        g2 = torch.Generator(device=dev)
+        g2.manual_seed(wl.SEED_LM_HEAD)
+        hid = cfg.hidden
+        h_t = torch.randn((B * (gmax + 1), hid), device=dev, generator=g2).to(torch.bfloat16)
+        w_t = (torch.randn((V, hid), device=dev, generator=g2) * (cfg.logit_std / math.sqrt(hid))).to(torch.bfloat16)
+        zt, st_t = r.rapid_lm_head(h_t, w_t, temperature=cfg.temperature)      # the step overwrites both
+        zt = zt.reshape(B, gmax + 1, V)
+        if cfg.draft_noise_std is not None and gmax > 0:
+            zd = (zt[:, :gmax] + torch.randn((B, gmax, V), device=dev, generator=g2) * cfg.draft_noise_std).contiguous()
+            gumbel = -torch.log(-torch.log(torch.rand((B, gmax, V), device=dev, generator=g2).clamp_min(1e-20)))
+            draft_tokens = torch.argmax(zd / cfg.temperature + gumbel, dim=-1).to(torch.int32)
+            del gumbel
+        head = (h_t, w_t, st_t)
     n_acc = torch.empty(B, dtype=torch.int32, device=dev)
     out_tok = torch.empty((B, gmax + 1), dtype=torch.int32, device=dev)
     ratio = torch.empty((B, gmax), dtype=torch.float32, device=dev)
@@ -143,6 +165,11 @@ def main():
                 float(cfg.temperature), float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), P(ratio),
                 P(ws), ws.numel(), stream)
 
+    if head:
+        head_args = (r._ctx, B * (gmax + 1), cfg.hidden, V, P(head[0]), P(head[1]), float(cfg.temperature),
+                     P(zt), V, P(head[2]), stream)
+        acc_pre_args = acc_args[:12] + (P(head[2]), head[2].shape[1], None, 0) + acc_args[12:]
+
     def check(rc):
         if rc != 0:
             raise RuntimeError(f"librapid status {rc}: {lib.rapid_strerror(rc).decode()}")
@@ -158,7 +185,13 @@ def main():
             check(lib.rapid_verify_attn(*a))
         if ev:
             ev[1].record()
-        check(lib.rapid_accept(*acc_args))
+        if head:
+            check(lib.rapid_lm_head(*head_args))
+            if ev:
+                ev[3].record()
+            check(lib.rapid_accept_prestats(*acc_pre_args))
+        else:
+            check(lib.rapid_accept(*acc_args))
         if ev:
             ev[2].record()
 
@@ -171,7 +204,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t_begin = torch.cuda.Event(enable_timing=True)
     t_end = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -183,7 +216,8 @@ def main():
     total_ms = t_begin.elapsed_time(t_end)
     ms_per_step = total_ms / args.steps
     attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps      # all layers of one step
-    acc_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    head_ms = sum(e[1].elapsed_time(e[3]) for e in evs) / args.steps if head else 0.0
+    acc_ms = sum(e[3 if head else 1].elapsed_time(e[2]) for e in evs) / args.steps
 
     # measured ceiling: 2 GiB streamed with no arithmetic, in launches as large as one attention call's
     # cache traffic (so launch and ramp-up cost weigh the same), never the same bytes twice in a row
@@ -236,8 +270,17 @@ def main():
         "roofline_accept": {"bound": "hbm", "kernel": "rapid_accept (all kernels of one call)",
                             "achieved": round(acc_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                             "frac": round(acc_gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes_per_launch": logit_bytes,
-                            "traffic": profile_traffic("rapid_accept") if profiled else None},
+                            "traffic": profile_traffic("rapid_accept") if profiled and not head else None},
     }
+
+    if head:
+        w_bytes = V * cfg.hidden * 2
+        result["config"]["lm_head"] = {"hidden": cfg.hidden, "rows": B * (gmax + 1), "weight_bytes": w_bytes}
+        result["breakdown_us"]["lm_head"] = round(head_ms * 1e3, 2)
+        result["roofline_lm_head"] = {"bound": "hbm", "kernel": "rapid_lm_head (lm_head_stream)",
+                                      "achieved": round(w_bytes / (head_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                                      "unit": "GB/s", "frac": round(w_bytes / (head_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                      "algorithmic_bytes_per_launch": w_bytes, "traffic": None}
 
     # ---------------------------------------------------------------- oracle on the host cores (baseline only)
     if not args.no_cpu_baseline:

@@ -153,6 +153,56 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                  int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* Vocabulary entries per statistics chunk of rapid_lm_head. */
+#define RAPID_LM_HEAD_CHUNK 512
+
+/* Number of statistics chunks per row that rapid_lm_head writes: ceil(vocab / 512); 0 if vocab < 1. */
+int rapid_lm_head_stat_chunks(int vocab);
+
+/*
+ * Output head for the verification rows: what Alg. 1 calls LogitsOf(p(. | [C; x_<j])),
+ * taken as the final hidden state times the output embedding (no bias; the final
+ * normalisation layer is the caller's):
+ *     logits[r][v] = sum_k h[r][k] * w[v][k]      bf16 inputs, fp32 accumulation
+ * and, when `stats` is given, per row and per chunk c of 512 consecutive entries
+ *     stats[r][c] = ( max_v logits[r][v], sum_v exp((logits[r][v] - max) / temperature) )
+ * which is what rapid_accept_prestats consumes (the pieces of softmax(z/T), Alg. 1).
+ *
+ *   n_rows       1..16 (e.g. gamma+1 rows of one sequence, ordered [sequence][position])
+ *   hidden       a multiple of 1024
+ *   vocab        >= 16
+ *   h            bf16 [n_rows, hidden], contiguous, 16-byte aligned
+ *   w            bf16 [vocab, hidden], contiguous, 16-byte aligned
+ *   temperature  > 0 (used only for the statistics)
+ *   logits       fp32, row r at logits + r * logits_row_stride (elements, >= vocab)
+ *   stats        fp32 [n_rows, rapid_lm_head_stat_chunks(vocab), 2] or NULL
+ * No workspace.  RAPID_EUNSUPPORTED for row counts or hidden sizes outside the above.
+ */
+int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
+                  const void* h, const void* w, float temperature,
+                  float* logits, int64_t logits_row_stride, float* stats, void* stream);
+
+/*
+ * rapid_accept with the (max, sum exp) statistics of the rows supplied by the caller
+ * instead of being formed from the logits by a first pass (same results up to the
+ * rounding order of the fp32 sums inside a chunk):
+ *   target_stats fp32 [B*(gamma_max+1), target_chunks, 2] or NULL; row b*(gamma_max+1)+k
+ *   draft_stats  fp32 [B*gamma_max,     draft_chunks,  2] or NULL
+ * each pair = (max of the raw logits of the chunk, sum exp((z - max)/temperature)) for ANY
+ * partition of the vocabulary into chunks (an empty chunk: sum 0); the temperature must be the
+ * one passed here.  A NULL side is computed from the logits as in rapid_accept.  Everything
+ * else, including the workspace size, is as for rapid_accept.
+ */
+int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
+                          const float* target_logits, const float* draft_logits,
+                          const int32_t* draft_tokens, const int32_t* gammas,
+                          float eta, float temperature, float tail_alpha,
+                          const float* uniforms,
+                          const float* target_stats, int target_chunks,
+                          const float* draft_stats, int draft_chunks,
+                          int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * Measurement aid, not part of the method: reads `bytes` bytes of device memory at
  * `buf` once, with the load path of rapid_verify_attn (HBM -> LDS, streaming hint)

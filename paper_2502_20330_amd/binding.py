@@ -19,7 +19,8 @@ RAPID_OK = 0
 RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP = -1, -2, -3, -4, -5
 EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
-           "rapid_accept_workspace_bytes", "rapid_accept", "rapid_hbm_read_probe"]
+           "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
+           "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_hbm_read_probe"]
 
 
 class RapidError(RuntimeError):
@@ -73,6 +74,16 @@ def load_library() -> ctypes.CDLL:
                                  ctypes.c_float, ctypes.c_float, ctypes.c_float, f32p, i32p, i32p, f32p,
                                  vp, ctypes.c_size_t, vp]
     lib.rapid_accept.restype = ctypes.c_int
+    lib.rapid_accept_prestats.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, f32p, f32p, i32p, i32p,
+                                          ctypes.c_float, ctypes.c_float, ctypes.c_float, f32p,
+                                          f32p, ctypes.c_int, f32p, ctypes.c_int, i32p, i32p, f32p,
+                                          vp, ctypes.c_size_t, vp]
+    lib.rapid_accept_prestats.restype = ctypes.c_int
+    lib.rapid_lm_head_stat_chunks.argtypes = [ctypes.c_int]
+    lib.rapid_lm_head_stat_chunks.restype = ctypes.c_int
+    lib.rapid_lm_head.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_float,
+                                  f32p, ctypes.c_int64, f32p, vp]
+    lib.rapid_lm_head.restype = ctypes.c_int
     lib.rapid_hbm_read_probe.argtypes = [ctypes.c_void_p, vp, ctypes.c_size_t, vp, vp]
     lib.rapid_hbm_read_probe.restype = ctypes.c_int
     _lib = lib
@@ -181,9 +192,12 @@ class Rapid:
 
     # ------------------------------------------------------------------ accept
     def rapid_accept(self, target_logits, draft_logits, draft_tokens, eta: float, uniforms, *, gammas=None,
-                     temperature: float = 1.0, tail_alpha: float = 0.1, want_ratio: bool = True, outs=None):
+                     temperature: float = 1.0, tail_alpha: float = 0.1, want_ratio: bool = True, outs=None,
+                     target_stats=None, draft_stats=None):
         """target_logits fp32 [B,g+1,V], draft_logits fp32 [B,g,V], draft_tokens int32 [B,g],
-        uniforms fp32 [B,g+1].  Returns (n_accepted int32 [B], out_tokens int32 [B,g+1], ratio fp32 [B,g] or None)."""
+        uniforms fp32 [B,g+1].  Returns (n_accepted int32 [B], out_tokens int32 [B,g+1], ratio fp32 [B,g] or None).
+        target_stats / draft_stats: optional fp32 [rows, chunks, 2] row statistics (see rapid_lm_head); with
+        either one the call goes to rapid_accept_prestats."""
         B, g1, V = target_logits.shape
         g = g1 - 1
         assert target_logits.dtype == torch.float32 and target_logits.is_contiguous()
@@ -200,12 +214,43 @@ class Rapid:
             n_acc, toks, ratio = outs
         need = self.lib.rapid_accept_workspace_bytes(self._ctx, B, g, V)
         ws = self._workspace(need)
-        rc = self.lib.rapid_accept(self._ctx, B, g, V, _dptr(target_logits), _dptr(draft_logits),
-                                   _dptr(draft_tokens), _dptr(gammas), float(eta), float(temperature),
-                                   float(tail_alpha), _dptr(uniforms), _dptr(n_acc), _dptr(toks), _dptr(ratio),
-                                   _dptr(ws), ws.numel(), _stream_ptr(self.device))
+        if target_stats is None and draft_stats is None:
+            rc = self.lib.rapid_accept(self._ctx, B, g, V, _dptr(target_logits), _dptr(draft_logits),
+                                       _dptr(draft_tokens), _dptr(gammas), float(eta), float(temperature),
+                                       float(tail_alpha), _dptr(uniforms), _dptr(n_acc), _dptr(toks), _dptr(ratio),
+                                       _dptr(ws), ws.numel(), _stream_ptr(self.device))
+        else:
+            for st, rows in ((target_stats, B * (g + 1)), (draft_stats, B * g)):
+                assert st is None or (st.dtype == torch.float32 and st.is_contiguous() and st.dim() == 3
+                                      and st.shape[0] == rows and st.shape[2] == 2)
+            rc = self.lib.rapid_accept_prestats(
+                self._ctx, B, g, V, _dptr(target_logits), _dptr(draft_logits), _dptr(draft_tokens), _dptr(gammas),
+                float(eta), float(temperature), float(tail_alpha), _dptr(uniforms),
+                _dptr(target_stats), 0 if target_stats is None else target_stats.shape[1],
+                _dptr(draft_stats), 0 if draft_stats is None else draft_stats.shape[1],
+                _dptr(n_acc), _dptr(toks), _dptr(ratio), _dptr(ws), ws.numel(), _stream_ptr(self.device))
         _check(self.lib, rc, self._ctx)
         return n_acc, toks, ratio
+
+    # ------------------------------------------------------------------ output head
+    def rapid_lm_head(self, h, w, *, temperature: float = 1.0, want_stats: bool = True, logits=None, stats=None):
+        """h bf16 [rows, hidden], w bf16 [vocab, hidden] -> (logits fp32 [rows, vocab],
+        stats fp32 [rows, ceil(vocab/512), 2] or None)."""
+        rows, hidden = h.shape
+        vocab = w.shape[0]
+        assert h.dtype == torch.bfloat16 and w.dtype == torch.bfloat16 and h.is_contiguous() and w.is_contiguous()
+        assert w.shape[1] == hidden
+        if logits is None:
+            logits = torch.empty(rows, vocab, dtype=torch.float32, device=self.device)
+        assert logits.dtype == torch.float32 and logits.stride(-1) == 1 and logits.shape == (rows, vocab)
+        if want_stats and stats is None:
+            stats = torch.empty(rows, self.lib.rapid_lm_head_stat_chunks(vocab), 2, dtype=torch.float32,
+                                device=self.device)
+        rc = self.lib.rapid_lm_head(self._ctx, rows, hidden, vocab, _dptr(h), _dptr(w), float(temperature),
+                                    _dptr(logits), logits.stride(0) if rows > 1 else vocab,
+                                    _dptr(stats) if want_stats else None, _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return logits, (stats if want_stats else None)
 
     # ------------------------------------------------------------------ measurement aid
     def rapid_hbm_read_probe(self, buf: torch.Tensor, nbytes: Optional[int] = None):
@@ -231,6 +276,11 @@ def _get(device: int = 0) -> Rapid:
 def rapid_verify_attn(q, k_cache, v_cache, ctx_lens, gamma=None, **kw):
     """Module-level form of :meth:`Rapid.rapid_verify_attn` on the tensors' device."""
     return _get(q.device.index or 0).rapid_verify_attn(q, k_cache, v_cache, ctx_lens, gamma, **kw)
+
+
+def rapid_lm_head(h, w, **kw):
+    """Module-level form of :meth:`Rapid.rapid_lm_head` on the tensors' device."""
+    return _get(h.device.index or 0).rapid_lm_head(h, w, **kw)
 
 
 def rapid_accept(target_logits, draft_logits, draft_tokens, eta, uniforms, **kw):

@@ -102,7 +102,8 @@ struct Ws {
     double* rows;     // [B][gmax+1][8]: zmax_t, lse_p, zmax_d, lse_q, lse_h, 1/S_h (= max p_hat), -, -
     double* wsum;     // [B][nch*kSubs][2]: per 256 entries, sum of residual weights and sum of p (fallback)
     int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
-    int nch;
+    int nch;          // chunks of kChunk entries (st_h, wsum)
+    int nch_t, nch_d; // chunks of st_t / st_d: nch, or the caller's when the statistics come from outside
 };
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -111,6 +112,7 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
 {
     Ws w;
     w.nch = (V + kChunk - 1) / kChunk;
+    w.nch_t = w.nch_d = w.nch;
     char* p = static_cast<char*>(base);
     w.st_t = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax + 1) * w.nch * sizeof(float2));
     w.st_d = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
@@ -130,6 +132,7 @@ __global__ void __launch_bounds__(kThreads) accept_row_stats(AcceptLaunch a, Ws 
     const bool is_t = y <= a.gmax;
     const int k = is_t ? y : y - (a.gmax + 1);
     if (is_t ? (k > g) : (k >= g)) return;
+    if (is_t ? a.ext_t != nullptr : a.ext_d != nullptr) return;    // this side's statistics were supplied
     const float* row = is_t ? a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V
                             : a.zd + ((int64_t)b * a.gmax + k) * a.V;
     const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15) == 0);
@@ -175,14 +178,12 @@ __device__ __forceinline__ void combine_row(const float2* st, int nch, double in
 // ---------------------------------------------------------------- K2
 // Row statistics of the target and the draft row, combined in fp32 by every workgroup
 // (enough for the elementwise pass; the decisions later use the fp64 combine of K3).
-__device__ __forceinline__ void combine_pair_f32(const float2* st_t, const float2* st_d, int nch, float inv_T,
+__device__ __forceinline__ void combine_pair_f32(const float2* st_t, int nt, const float2* st_d, int nd, float inv_T,
                                                  float* sh, float& Mt, float& lnSt, float& Md, float& lnSd)
 {
     float mt = -INFINITY, md = -INFINITY;
-    for (int i = threadIdx.x; i < nch; i += kThreads) {
-        mt = fmaxf(mt, st_t[i].x);
-        md = fmaxf(md, st_d[i].x);
-    }
+    for (int i = threadIdx.x; i < nt; i += kThreads) mt = fmaxf(mt, st_t[i].x);
+    for (int i = threadIdx.x; i < nd; i += kThreads) md = fmaxf(md, st_d[i].x);
     mt = wave_max(mt);
     md = wave_max(md);
     __syncthreads();
@@ -191,9 +192,12 @@ __device__ __forceinline__ void combine_pair_f32(const float2* st_t, const float
     Mt = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
     Md = fmaxf(fmaxf(sh[4], sh[5]), fmaxf(sh[6], sh[7]));
     float st = 0.f, sd = 0.f;
-    for (int i = threadIdx.x; i < nch; i += kThreads) {
-        float2 t = st_t[i], d = st_d[i];
+    for (int i = threadIdx.x; i < nt; i += kThreads) {
+        float2 t = st_t[i];
         if (t.y > 0.f) st += t.y * fexp((t.x - Mt) * inv_T);
+    }
+    for (int i = threadIdx.x; i < nd; i += kThreads) {
+        float2 d = st_d[i];
         if (d.y > 0.f) sd += d.y * fexp((d.x - Md) * inv_T);
     }
     st = wave_sum(st);
@@ -222,8 +226,8 @@ __global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a,
         y[v] = load4(zd, i0, a.V, vec);
     }
     float zmax_t, lnS_t, zmax_d, lnS_d;
-    combine_pair_f32(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch,
-                     ws.nch, a.inv_T, sh, zmax_t, lnS_t, zmax_d, lnS_d);
+    combine_pair_f32(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch_t, ws.nch_t,
+                     ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch_d, ws.nch_d, a.inv_T, sh, zmax_t, lnS_t, zmax_d, lnS_d);
     float m = -INFINITY;
 #pragma unroll
     for (int v = 0; v < kVec; ++v)
@@ -281,9 +285,9 @@ __global__ void __launch_bounds__(64) accept_decide(AcceptLaunch a, Ws ws)
         }
     }
     double Mt, St, Md = 0, Sd = 1, Mh = 0, Sh = 1;
-    wave_combine(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch, ws.nch, a.inv_T_exact, Mt, St);
+    wave_combine(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch_t, ws.nch_t, a.inv_T_exact, Mt, St);
     if (k < g) {
-        wave_combine(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, a.inv_T_exact, Md, Sd);
+        wave_combine(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch_d, ws.nch_d, a.inv_T_exact, Md, Sd);
         wave_combine(ws.st_h + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, 1.0, Mh, Sh);
     }
     if (threadIdx.x != 0) return;
@@ -516,8 +520,11 @@ size_t accept_workspace_bytes(int B, int gmax, int V)
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
 {
     Ws ws = carve(a.workspace, a.B, a.gmax, a.V);
+    if (a.ext_t) { ws.st_t = reinterpret_cast<float2*>(const_cast<float*>(a.ext_t)); ws.nch_t = a.nch_t; }
+    if (a.ext_d) { ws.st_d = reinterpret_cast<float2*>(const_cast<float*>(a.ext_d)); ws.nch_d = a.nch_d; }
     dim3 blk(kThreads);
-    hipLaunchKernelGGL(accept_row_stats, dim3(ws.nch, 2 * a.gmax + 1, a.B), blk, 0, stream, a, ws);
+    if (!a.ext_t || (a.gmax > 0 && !a.ext_d))
+        hipLaunchKernelGGL(accept_row_stats, dim3(ws.nch, 2 * a.gmax + 1, a.B), blk, 0, stream, a, ws);
     if (a.gmax > 0)
         hipLaunchKernelGGL(accept_shifted_stats, dim3(ws.nch, a.gmax, a.B), blk, 0, stream, a, ws);
     hipLaunchKernelGGL(accept_decide, dim3(a.gmax + 1, a.B), dim3(64), 0, stream, a, ws);

@@ -1,0 +1,273 @@
+// Output head of the target model for the verification rows, for gfx950 (MI355X):
+//     z[r][v] = sum_k h[r][k] * W[v][k]          ("LogitsOf", Alg. 1)
+// for the few rows of a verification step (gamma+1 <= 16), with the per-chunk
+// softmax statistics of every row (max z, sum exp((z - max)/T)) produced in the
+// epilogue, so that the acceptance pass does not have to read the logits once more
+// to form them.
+//
+// With at most 16 rows this is a matrix-vector problem: every weight is used 2 x rows
+// times, so the kernel is bound by streaming W (vocab x hidden bf16, about 1 GB for a
+// 128K vocabulary) from HBM.  Design:
+//
+//  * One workgroup owns 512 consecutive vocabulary rows (4 MiB of W at hidden = 4096).
+//    Its four waves split the hidden dimension in quarters: a wave reads 2*hidden/4
+//    contiguous bytes of every row, 512 B at a time.
+//  * W travels HBM -> LDS directly (global_load_lds_dwordx4, 1 KiB per instruction)
+//    in tiles of 16 rows x 256 k (8 KiB) through a four-slot ring per wave, three tiles
+//    ahead of the math; the wave counts its own outstanding loads, so the main loop has
+//    no workgroup barrier.
+//  * The matching 256-k slab of h (16 rows, rows past the last real one repeat it)
+//    comes through the same ring as one more tile at the head of every slab and is
+//    then held in registers as the B operand of v_mfma_f32_16x16x32_bf16 for the 32
+//    W tiles that follow; the accumulators of all 32 row blocks (128 registers) stay in
+//    registers across slabs.
+//  * A 16-byte-chunk XOR swizzle applied by the load addressing makes the operand reads
+//    (ds_read_b128, 16 rows of 512 B) bank-conflict free without padding.
+//  * Epilogue: the four K-quarter partial sums meet in LDS, are added in a fixed
+//    order, stored as fp32 logits, and reduced to the chunk's (max, sum exp) per row.
+#include "rapid_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kNB = 32;                      // 16-row vocabulary blocks per workgroup
+constexpr int kVB = kNB * 16;                // vocabulary rows per workgroup (= statistics chunk)
+constexpr int kSlabK = 256;                  // hidden elements per tile row
+constexpr int kTileBytes = 16 * kSlabK * 2;  // 8 KiB
+constexpr int kSlots = 4;
+constexpr int kRing = kSlots * kTileBytes;   // per wave
+constexpr int kVBP = kVB + 4;                // padded row of the epilogue buffer (floats)
+constexpr float kLog2e = 1.4426950408889634f;
+
+static_assert(kVB == RAPID_LM_HEAD_CHUNK, "public chunk size and kernel tile disagree");
+
+constexpr int lds_bytes()
+{
+    constexpr int ring = kWaves * kRing;
+    constexpr int epi = kWaves * 16 * kVBP * 4 + 2 * kWaves * 16 * 4;
+    return ring > epi ? ring : epi;
+}
+
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+// h is re-read by every workgroup: no streaming hint, it should stay in cache
+__device__ __forceinline__ void dma16_keep(const char* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void lds_reads_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ln = lane & 15, lg = lane >> 4;
+    const int v0 = blockIdx.x * kVB;
+    const uint32_t row_bytes = (uint32_t)a.hidden * 2u;
+    const int kq = wave * (a.hidden / kWaves);          // first hidden element of this wave's quarter
+    const int nslab = a.hidden / (kWaves * kSlabK);
+    char* ring = smem + wave * kRing;
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * kRing;
+
+    // Per-lane byte offsets of the eight loads of a tile, relative to the tile's first
+    // row and first k: instruction e moves rows 2e and 2e+1; lane i writes LDS bytes
+    // [16 i, 16 i + 16) of that 1 KiB and fetches the chunk the swizzle assigns there.
+    uint32_t woff[8], hoff[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int r = 2 * e + (lane >> 5);
+        const uint32_t c = (uint32_t)((lane & 31) ^ (r & 15)) * 16u;
+        woff[e] = (uint32_t)r * row_bytes + c;
+        hoff[e] = (uint32_t)min(r, a.n_rows - 1) * row_bytes + c;
+    }
+
+    // tile j of slab s: j = 0 is the h slab, j = 1..kNB the W row blocks
+    auto issue = [&](int s, int j, int slot) {
+        const int64_t kbyte = (int64_t)(kq + s * kSlabK) * 2;
+        const uint32_t dst = ring_lds + slot * kTileBytes;
+        if (j == 0) {
+            const char* base = reinterpret_cast<const char*>(a.h) + kbyte;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dma16_keep(base, hoff[e], dst + e * 1024);
+            return;
+        }
+        // A block that reaches past the vocabulary reads the last 16 rows instead: its
+        // rows are then shifted against the block's nominal ones, which the epilogue
+        // undoes; a block wholly past the end is never stored.
+        const int row0 = min(v0 + (j - 1) * 16, a.vocab - 16);
+        const char* base = reinterpret_cast<const char*>(a.w) + (int64_t)row0 * row_bytes + kbyte;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dma16(base, woff[e], dst + e * 1024);
+    };
+
+    issue(0, 0, 0);
+    issue(0, 1, 1);
+    issue(0, 2, 2);
+
+    floatx4 acc[kNB];
+#pragma unroll
+    for (int j = 0; j < kNB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 hreg[8];
+    // operand read: lane (ln, lg) takes row ln, chunk 4 ks + lg of the 32 chunks of a row
+    const int rd_row = ln * (kSlabK * 2);
+    const int rd_swz = ln & 15;
+
+    for (int s = 0; s < nslab; ++s) {
+        const int slot0 = (s * (kNB + 1)) & (kSlots - 1);
+        const bool more = s + 1 < nslab;
+#pragma unroll
+        for (int j = 0; j <= kNB; ++j) {
+            wait_loads<16>();                                  // tile (s, j) has landed
+            // three tiles ahead, into the slot whose reads finished last iteration
+            {
+                const int jn = j + 3, sl = (slot0 + j + 3) & (kSlots - 1);
+                if (jn <= kNB) issue(s, jn, sl);
+                else if (more) issue(s + 1, jn - (kNB + 1), sl);
+                else issue(s, 0, sl);                          // nothing left: a cached h tile keeps the count
+            }
+            const char* tile = ring + ((slot0 + j) & (kSlots - 1)) * kTileBytes;
+            if (j == 0) {
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    hreg[ks] = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    bf16x8 wa = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
+                    acc[j - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, hreg[ks], acc[j - 1], 0, 0, 0);
+                }
+            }
+            lds_reads_done();
+        }
+    }
+    wait_loads<0>();
+    __syncthreads();                                           // the ring is dead from here on
+
+    // ---- the four K quarters meet: zbuf[wave][row n][vocabulary entry], padded rows
+    float* zbuf = reinterpret_cast<float*>(smem);
+    float* red = zbuf + kWaves * 16 * kVBP;                    // [2][kWaves][16]
+#pragma unroll
+    for (int j = 0; j < kNB; ++j)
+        *reinterpret_cast<floatx4*>(zbuf + (wave * 16 + ln) * kVBP + j * 16 + lg * 4) = acc[j];
+    __syncthreads();
+
+    constexpr int kPer = kVB / (kWaves * 64);                  // vocabulary entries per thread
+    float z[16][kPer];
+    float mx[16];
+    int col[kPer];                                             // where this thread's entries sit in zbuf
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int vl = tid + u * (kWaves * 64);
+        const int nominal = v0 + (vl & ~15);                   // first row of the entry's block
+        col[u] = vl + max(0, nominal - (a.vocab - 16));        // shifted block at the end of the vocabulary
+    }
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+        mx[n] = -INFINITY;
+        if (n < a.n_rows) {
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int vl = tid + u * (kWaves * 64);
+                float x = 0.f;
+                if (v0 + vl < a.vocab) {
+                    x = zbuf[(0 * 16 + n) * kVBP + col[u]];
+#pragma unroll
+                    for (int w = 1; w < kWaves; ++w) x += zbuf[(w * 16 + n) * kVBP + col[u]];
+                    a.logits[(int64_t)n * a.ldz + v0 + vl] = x;
+                    mx[n] = fmaxf(mx[n], x);
+                }
+                z[n][u] = x;
+            }
+            mx[n] = wave_max(mx[n]);
+        }
+    }
+    if (!a.stats) return;
+    if (lane < 16) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int n = 0; n < 16; ++n) m = lane == n ? mx[n] : m;
+        red[wave * 16 + lane] = m;
+    }
+    __syncthreads();
+    float sm[16];
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+        sm[n] = 0.f;
+        if (n < a.n_rows) {
+            const float M = fmaxf(fmaxf(red[n], red[16 + n]), fmaxf(red[32 + n], red[48 + n]));
+            mx[n] = M;
+            float sacc = 0.f;
+#pragma unroll
+            for (int u = 0; u < kPer; ++u)
+                if (v0 + tid + u * (kWaves * 64) < a.vocab)
+                    sacc += __builtin_amdgcn_exp2f((z[n][u] - M) * a.inv_T * kLog2e);
+            sm[n] = wave_sum(sacc);
+        }
+    }
+    float* red2 = red + kWaves * 16;
+    if (lane < 16) {
+        float sv = 0.f;
+#pragma unroll
+        for (int n = 0; n < 16; ++n) sv = lane == n ? sm[n] : sv;
+        red2[wave * 16 + lane] = sv;
+    }
+    __syncthreads();
+    if (tid < a.n_rows) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int n = 0; n < 16; ++n) M = tid == n ? mx[n] : M;
+        const float S = (red2[tid] + red2[16 + tid]) + (red2[32 + tid] + red2[48 + tid]);
+        a.stats[((int64_t)tid * gridDim.x + blockIdx.x) * 2 + 0] = M;
+        a.stats[((int64_t)tid * gridDim.x + blockIdx.x) * 2 + 1] = S;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
+{
+    constexpr int lds = lds_bytes();
+    static bool configured[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 64 && !configured[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        configured[dev] = true;
+    }
+    const int nwg = (a.vocab + kVB - 1) / kVB;
+    hipLaunchKernelGGL(lm_head_stream, dim3(nwg), dim3(kWaves * 64), lds, stream, a);
+    return hipGetLastError();
+}

@@ -200,19 +200,23 @@ size_t rapid_accept_workspace_bytes(const rapid_ctx*, int batch, int gamma_max, 
     return accept_workspace_bytes(batch, gamma_max, vocab);
 }
 
-int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
-                 const float* target_logits, const float* draft_logits,
-                 const int32_t* draft_tokens, const int32_t* gammas,
-                 float eta, float temperature, float tail_alpha,
-                 const float* uniforms,
-                 int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
-                 void* workspace, size_t workspace_bytes, void* stream)
+int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
+                          const float* target_logits, const float* draft_logits,
+                          const int32_t* draft_tokens, const int32_t* gammas,
+                          float eta, float temperature, float tail_alpha,
+                          const float* uniforms,
+                          const float* target_stats, int target_chunks,
+                          const float* draft_stats, int draft_chunks,
+                          int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
+                          void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!ctx || batch < 1 || gamma_max < 0 || vocab < 1) return RAPID_EINVAL;
     if (!target_logits || !uniforms || !n_accepted || !out_tokens) return RAPID_EINVAL;
     if (gamma_max > 0 && (!draft_logits || !draft_tokens)) return RAPID_EINVAL;
     if (!(eta >= 0.f) || !(temperature > 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
+    if ((target_stats && target_chunks < 1) || (draft_stats && draft_chunks < 1)) return RAPID_EINVAL;
     if (!aligned(target_logits, 4) || !aligned(draft_logits, 4)) return RAPID_EALIGN;
+    if (!aligned(target_stats, 8) || !aligned(draft_stats, 8)) return RAPID_EALIGN;
     const size_t need = accept_workspace_bytes(batch, gamma_max, vocab);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return RAPID_EWORKSPACE;
 
@@ -233,7 +237,52 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     a.inv_T_exact = 1.0 / (double)temperature;
     a.inv_T = (float)a.inv_T_exact;
     a.tail_alpha = tail_alpha;
+    a.ext_t = target_stats;
+    a.nch_t = target_chunks;
+    a.ext_d = gamma_max > 0 ? draft_stats : nullptr;
+    a.nch_d = draft_chunks;
     hipError_t e = launch_accept(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
+int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
+                 const float* target_logits, const float* draft_logits,
+                 const int32_t* draft_tokens, const int32_t* gammas,
+                 float eta, float temperature, float tail_alpha,
+                 const float* uniforms,
+                 int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
+                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    return rapid_accept_prestats(ctx, batch, gamma_max, vocab, target_logits, draft_logits, draft_tokens, gammas,
+                                 eta, temperature, tail_alpha, uniforms, nullptr, 0, nullptr, 0,
+                                 n_accepted, out_tokens, accept_ratio, workspace, workspace_bytes, stream);
+}
+
+int rapid_lm_head_stat_chunks(int vocab)
+{
+    return vocab < 1 ? 0 : (vocab + RAPID_LM_HEAD_CHUNK - 1) / RAPID_LM_HEAD_CHUNK;
+}
+
+int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
+                  const void* h, const void* w, float temperature,
+                  float* logits, int64_t logits_row_stride, float* stats, void* stream)
+{
+    if (!ctx || !h || !w || !logits) return RAPID_EINVAL;
+    if (n_rows < 1 || hidden < 1 || vocab < 1 || logits_row_stride < vocab || !(temperature > 0.f)) return RAPID_EINVAL;
+    if (n_rows > 16 || hidden % 1024 || vocab < 16) return RAPID_EUNSUPPORTED;
+    if (!aligned(h, 16) || !aligned(w, 16) || !aligned(logits, 4) || !aligned(stats, 8)) return RAPID_EALIGN;
+    LmHeadLaunch a{};
+    a.h = static_cast<const uint16_t*>(h);
+    a.w = static_cast<const uint16_t*>(w);
+    a.logits = logits;
+    a.stats = stats;
+    a.n_rows = n_rows;
+    a.hidden = hidden;
+    a.vocab = vocab;
+    a.ldz = logits_row_stride;
+    a.inv_T = (float)(1.0 / (double)temperature);
+    hipError_t e = launch_lm_head(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
 }

@@ -47,9 +47,26 @@ struct AcceptLaunch {
     int32_t B, gmax, V;
     float eta, inv_T, tail_alpha;
     double inv_T_exact;   // 1 / (double)temperature
+    // row statistics computed elsewhere (the output head's epilogue), or null:
+    // (max z, sum exp((z - max)/T)) per chunk, [B*(gmax+1)][nch_t] and [B*gmax][nch_d] pairs
+    const float* ext_t;
+    const float* ext_d;
+    int32_t nch_t, nch_d;
 };
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int gmax, int V);
 
 // ---- streaming-read probe (hbm_probe.hip)
 hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream);
+
+// ---- output head (lm_head.hip)
+struct LmHeadLaunch {
+    const uint16_t* h;      // [n_rows][hidden] bf16
+    const uint16_t* w;      // [vocab][hidden] bf16
+    float* logits;          // [n_rows][ldz]
+    float* stats;           // [n_rows][ceil(vocab/512)][2] or null
+    int32_t n_rows, hidden, vocab;
+    int64_t ldz;
+    float inv_T;
+};
+hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream);

@@ -46,6 +46,7 @@ class VerifyConfig:
     temperature: float = 1.0
     tail_alpha: float = 0.1
     etas: Tuple[float, ...] = field(default=())
+    hidden: int = 4096                   # model width (rows of the output head)
 
     @property
     def gamma_max(self) -> int:
@@ -79,7 +80,7 @@ CONFIGS = {
                                  128256, 1.0, 4.0, 1.0, k_scale=1.0 / math.sqrt(128), paged=True),
     "llama70b_128k_step": VerifyConfig("llama70b_128k_step", 80, 1, 64, 8, 128, (131072, 131072),
                                        (8,), 128256, 0.5, 4.0, 1.0, k_scale=1.0 / math.sqrt(128),
-                                       etas=(0.25, 0.5, 1.0)),
+                                       etas=(0.25, 0.5, 1.0), hidden=8192),
     # next rows: the drafter's own decode step on the retrieved context (Sec. 2.2: the drafter works on
     # the shortened context, one position per step): the same two calls at gamma = 0, where the accept
     # call reduces to drawing the next token from softmax(z / T)
@@ -220,3 +221,17 @@ def gen_accept_inputs(cfg: VerifyConfig, seqs: Optional[Sequences] = None, batch
         g2 = np.random.default_rng([SEED_PAGES, salt, 1])
         gam = g2.choice(np.asarray(cfg.gamma_choices, dtype=np.int32), size=B).astype(np.int32)
     return AcceptInputs(zt, zd, tok, u, gam)
+
+
+# ---------------------------------------------------------------- output head
+SEED_LM_HEAD = 5
+
+
+def gen_lm_head_inputs(rows: int, hidden: int, vocab: int, *, logit_std: float = 4.0, salt: int = 0):
+    """Final hidden states and output embedding as bf16 bit patterns: h ~ N(0, 1) [rows, hidden],
+    W ~ N(0, logit_std^2 / hidden) [vocab, hidden], so that the logits h W^T have standard deviation
+    logit_std like the synthetic logits of the accept workloads."""
+    rng = np.random.default_rng([SEED_LM_HEAD, salt])
+    h = _normal_bf16(rng, (rows, hidden))
+    w = _normal_bf16(rng, (vocab, hidden), scale=logit_std / math.sqrt(hidden))
+    return h, w

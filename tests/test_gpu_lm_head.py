@@ -1,0 +1,165 @@
+"""GPU parity: rapid_lm_head (C ABI, gfx950 kernel) against the float64 oracle, element by element,
+and the statistics it hands to rapid_accept_prestats.
+
+Tolerances.  Logits: bf16 x bf16 products are exact in fp32; the kernel adds `hidden` of them in fp32
+(MFMA accumulators, four K quarters added at the end), so the error is a few ulps of the largest partial
+sum: |gpu - ref| <= 5e-5 + 1e-5 |ref| for |z| up to ~25 and hidden up to 8192 (measured: below 8e-6; printed).
+Statistics: the chunk maximum must equal the maximum of the GPU's own logits bit for bit; the chunk sum is
+an fp32 sum of 512 exponentials, relative error <= 2e-5 against the float64 sum over the oracle's logits
+shifted by the GPU maximum."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_20330_amd import binding
+from paper_2502_20330_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 5e-5, 1e-5
+CH = 512
+
+gu = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    global gu
+    import gpu_util
+    gu = gpu_util
+    yield
+
+
+def run(rows, hidden, vocab, T=1.0, salt=0, what=""):
+    h, w = wl.gen_lm_head_inputs(rows, hidden, vocab, salt=salt)
+    hd, wd = gu.bf16_to_dev(h), gu.bf16_to_dev(w)
+    logits, stats = gu.rapid().rapid_lm_head(hd, wd, temperature=T)
+    torch.cuda.synchronize()
+    z = logits.cpu().numpy().astype(np.float64)
+    st = stats.cpu().numpy().astype(np.float64)
+    ref = oracle.lm_head(h, w)
+    err = np.abs(z - ref)
+    assert np.all(np.isfinite(z))
+    worst = np.unravel_index(np.argmax(err - RTOL * np.abs(ref)), err.shape)
+    assert np.all(err <= ATOL + RTOL * np.abs(ref)), \
+        f"{what}: max abs err {err.max():.3e} at {worst}: got {z[worst]:.6f} ref {ref[worst]:.6f}"
+    nch = (vocab + CH - 1) // CH
+    assert st.shape == (rows, nch, 2)
+    # chunk maxima: exactly the maxima of the logits the kernel wrote
+    pad = np.full((rows, nch * CH), -np.inf)
+    pad[:, :vocab] = z
+    assert np.array_equal(st[:, :, 0], pad.reshape(rows, nch, CH).max(axis=2)), what + ": chunk maxima"
+    # chunk sums against the oracle's definition on the oracle's logits, re-based to the GPU maximum
+    cmax, csum = oracle.chunk_stats(ref, CH, T)
+    ref_sum = csum * np.exp((cmax - st[:, :, 0]) / T)
+    np.testing.assert_allclose(st[:, :, 1], ref_sum, rtol=2e-5 + 2 * ATOL / T, err_msg=what + ": chunk sums")
+    print(f"[{what}] rows={rows} hidden={hidden} vocab={vocab} T={T}: max_abs={err.max():.3e} "
+          f"max|ref|={np.abs(ref).max():.2f}")
+    return z, st, (hd, wd)
+
+
+@pytest.mark.parametrize("vocab", [16, 17, 500, 512, 513, 1000, 1024, 1537, 4103])
+def test_vocabulary_edges(vocab):
+    run(9, 1024, vocab, what=f"vocab{vocab}")
+
+
+@pytest.mark.parametrize("rows", [1, 2, 5, 9, 11, 16])
+def test_row_counts(rows):
+    run(rows, 2048, 3000, salt=rows, what=f"rows{rows}")
+
+
+@pytest.mark.parametrize("hidden", [1024, 3072, 4096, 5120, 8192])
+def test_hidden_sizes(hidden):
+    run(9, hidden, 2500, salt=hidden, what=f"hidden{hidden}")
+
+
+@pytest.mark.parametrize("T", [0.1, 0.7, 2.0])
+def test_temperature_in_statistics(T):
+    run(4, 1024, 2000, T=T, what=f"T{T}")
+
+
+def test_strided_logits_rows_and_no_stats():
+    h, w = wl.gen_lm_head_inputs(3, 1024, 777, salt=3)
+    hd, wd = gu.bf16_to_dev(h), gu.bf16_to_dev(w)
+    big = torch.full((3, 1000), 7.0, dtype=torch.float32, device="cuda")
+    view = big[:, :777]
+    gu.rapid().rapid_lm_head(hd, wd, want_stats=False, logits=view)
+    torch.cuda.synchronize()
+    ref = oracle.lm_head(h, w)
+    got = big.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got[:, :777] - ref) <= ATOL + RTOL * np.abs(ref))
+    assert np.all(got[:, 777:] == 7.0), "elements past the vocabulary must not be written"
+
+
+def test_repeat_calls_are_bitwise_identical():
+    h, w = wl.gen_lm_head_inputs(9, 4096, 5000, salt=9)
+    hd, wd = gu.bf16_to_dev(h), gu.bf16_to_dev(w)
+    a, sa = gu.rapid().rapid_lm_head(hd, wd)
+    a, sa = a.clone(), sa.clone()
+    b, sb = gu.rapid().rapid_lm_head(hd, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(sa, sb)
+
+
+def test_bad_arguments_return_error_codes():
+    r = gu.rapid()
+    h = torch.zeros(17, 1024, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(64, 1024, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.RapidError) as e:
+        r.rapid_lm_head(h, w)
+    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # 17 rows
+    with pytest.raises(binding.RapidError) as e:
+        r.rapid_lm_head(h[:4, :1000].contiguous(), w[:, :1000].contiguous())
+    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # hidden not a multiple of 1024
+    with pytest.raises(binding.RapidError) as e:
+        r.rapid_lm_head(h[:4], w, temperature=0.0)
+    assert e.value.status == binding.RAPID_EINVAL
+
+
+def test_full_size_head_and_accept_with_its_statistics():
+    """LLaMA-3.1-8B head shape: 9 verification rows x 4096 hidden x 128256 entries.  Every logit against the
+    oracle; then the acceptance pass fed with the kernel's logits and statistics against (a) the same pass
+    forming its own statistics and (b) the oracle's accept on the very same logits."""
+    cfg = wl.CONFIGS["llama8b_128k_step"]
+    g, V = cfg.gamma_max, cfg.vocab
+    z, st, _ = run(g + 1, 4096, V, what="llama8b head")
+    zt = torch.from_numpy(z.astype(np.float32)).cuda().reshape(1, g + 1, V)
+    acc = wl.gen_accept_inputs(cfg)
+    # drafter logits: the same kernel, one row per drafter step, on hidden states that are the target's plus
+    # noise (so that drafts are accepted at a realistic rate); input construction only
+    h, w = wl.gen_lm_head_inputs(g + 1, 4096, V)
+    noise = np.random.default_rng(11).standard_normal((g, 4096)).astype(np.float32) * 0.25
+    hq = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(h[:g]) + noise)
+    zq, stq = gu.rapid().rapid_lm_head(gu.bf16_to_dev(hq), gu.bf16_to_dev(w))
+    zq_ref = oracle.lm_head(hq, w)
+    assert np.all(np.abs(zq.cpu().numpy() - zq_ref) <= ATOL + RTOL * np.abs(zq_ref))
+    # draft tokens: the drafter's own samples from softmax(zq), by the library's draw at gamma = 0
+    toks = []
+    u0 = torch.from_numpy(acc.uniforms[:, :g].copy()).cuda()
+    for k in range(g):
+        _, t, _ = gu.rapid().rapid_accept(zq[k].reshape(1, 1, V), torch.empty(1, 0, V, device="cuda"),
+                                          torch.empty(1, 0, dtype=torch.int32, device="cuda"), 0.0,
+                                          u0[:, k:k + 1].contiguous(), want_ratio=False)
+        toks.append(t[0, 0])
+    tok = torch.stack(toks).reshape(1, g).to(torch.int32)
+    u = torch.from_numpy(acc.uniforms).cuda()
+    zq3 = zq.reshape(1, g, V)
+    accepted = []
+    for eta in (0.0, 1.0, 5.0):
+        a = gu.rapid().rapid_accept(zt, zq3, tok, eta, u)
+        b = gu.rapid().rapid_accept(zt, zq3, tok, eta, u, target_stats=st_dev(st), draft_stats=stq)
+        torch.cuda.synchronize()
+        ref = oracle.accept(zt.cpu().numpy(), zq3.cpu().numpy(), tok.cpu().numpy(), acc.uniforms,
+                            eta=eta, temperature=1.0, tail_alpha=0.1)
+        for name, got in (("own statistics", a), ("head statistics", b)):
+            res = gu.compare_accept(tuple(x.cpu().numpy() if x is not None else None for x in got), ref, None, g)
+            assert res["n_mismatch"] == 0 and res["token_mismatch"] == 0, f"eta={eta} {name}: {res}"
+            assert res["max_ratio_rel_err"] < 1e-4, f"eta={eta} {name}: {res}"
+        print(f"[head+accept eta={eta}] n_accepted={int(b[0][0])} tokens={b[1][0].tolist()}")
+        accepted.append(int(b[0][0]))
+    assert max(accepted) > 0, "the correlated drafter should get some drafts accepted"
+
+
+def st_dev(st):
+    return torch.from_numpy(st.astype(np.float32)).cuda().contiguous()
