@@ -280,7 +280,8 @@ def main():
         result["roofline_lm_head"] = {"bound": "hbm", "kernel": "rapid_lm_head (lm_head_stream)",
                                       "achieved": round(w_bytes / (head_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                                       "unit": "GB/s", "frac": round(w_bytes / (head_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                                      "algorithmic_bytes_per_launch": w_bytes, "traffic": None}
+                                      "algorithmic_bytes_per_launch": w_bytes,
+                                      "traffic": profile_traffic("rapid_lm_head") if cfg.name == "llama8b_128k_step" else None}
 
     # ---------------------------------------------------------------- oracle on the host cores (baseline only)
     if not args.no_cpu_baseline:

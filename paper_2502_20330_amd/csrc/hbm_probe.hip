@@ -23,7 +23,7 @@ __global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, 
     const char* base = buf + b0 * kBlock;
     const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * 2 * kBlock;
     auto issue = [&](int t) {
-        const char* bp = base + (int64_t)(t < n ? t : n - 1) * kBlock;   // clamped: always inside the range
+        const char* bp = base + (int64_t)t * kBlock;
 #pragma unroll
         for (int e = 0; e < kBlock / 1024; ++e) {
             const uint32_t off = e * 1024 + lane * 16;
@@ -37,8 +37,12 @@ __global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, 
     issue(0);
     uint32_t acc = 0;
     for (int t = 0; t < n; ++t) {
-        issue(t + 1);
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");              // block t has landed
+        if (t + 1 < n) {
+            issue(t + 1);
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");          // block t has landed
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         acc ^= *reinterpret_cast<const uint32_t*>(smem + wave * 2 * kBlock + (t & 1) * kBlock + lane * 4);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
