@@ -45,6 +45,8 @@ def _load():
         lib.oracle_accept.restype = ctypes.c_int
         lib.oracle_distributions.restype = None
         lib.oracle_lm_head.restype = ctypes.c_int
+        lib.oracle_kv_append.restype = ctypes.c_int
+        lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_chunk_stats.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -185,3 +187,47 @@ def chunk_stats(z, chunk: int, temperature: float = 1.0):
     if rc != 0:
         raise ValueError(f"oracle_chunk_stats: invalid argument (rc={rc})")
     return cmax, csum
+
+
+def _c_layout(layout: KVLayout) -> _Layout:
+    return _Layout(layout.batch_stride, layout.token_stride, layout.head_stride, layout.page_size,
+                   layout.page_stride, layout.max_pages)
+
+
+def kv_append(k_cache, v_cache, k_new, v_new, ctx_lens, layout: KVLayout, *, gamma=None, gammas=None,
+              page_table=None):
+    """Writes rows 0..gamma_b of k_new/v_new (uint16 [B, Qmax, Hkv, d]) into the caches IN PLACE as the
+    last gamma_b+1 tokens of every sequence (ctx_lens counts them)."""
+    lib = _load()
+    for a in (k_cache, v_cache):
+        if a.dtype != np.uint16 or not a.flags.c_contiguous or not a.flags.writeable:
+            raise ValueError("caches must be writable C-contiguous uint16 arrays")
+    k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+    v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    B, Qmax, Hkv, d = k_new.shape
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    gammas = None if gammas is None else np.ascontiguousarray(gammas, dtype=np.int32)
+    page_table = None if page_table is None else np.ascontiguousarray(page_table, dtype=np.int32)
+    lay = _c_layout(layout)
+    rc = lib.oracle_kv_append(ctypes.c_int(B), ctypes.c_int(Qmax), ctypes.c_int(Hkv), ctypes.c_int(d),
+                              _ptr(k_new, ctypes.c_uint16), _ptr(v_new, ctypes.c_uint16),
+                              _ptr(ctx_lens, ctypes.c_int32), _ptr(gammas, ctypes.c_int32),
+                              ctypes.c_int(0 if gamma is None else gamma), ctypes.byref(lay),
+                              _ptr(page_table, ctypes.c_int32),
+                              _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_append: invalid argument (rc={rc})")
+
+
+def kv_commit(ctx_lens, n_accepted, *, gamma=None, gammas=None):
+    """Context lengths after a validation round that accepted n_accepted[b] drafts (new int32 array)."""
+    lib = _load()
+    out = np.array(ctx_lens, dtype=np.int32, copy=True)
+    n_accepted = np.ascontiguousarray(n_accepted, dtype=np.int32)
+    gammas = None if gammas is None else np.ascontiguousarray(gammas, dtype=np.int32)
+    rc = lib.oracle_kv_commit(ctypes.c_int(len(out)), _ptr(gammas, ctypes.c_int32),
+                              ctypes.c_int(0 if gamma is None else gamma),
+                              _ptr(n_accepted, ctypes.c_int32), _ptr(out, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_commit: invalid argument (rc={rc})")
+    return out

@@ -39,6 +39,14 @@
  *       max_v z and sum_v exp((z - max)/T): the pieces from which
  *       softmax(z/T) of Alg. 1 is normalised.
  *
+ *   oracle_kv_append / oracle_kv_commit -- the cache bookkeeping Alg. 1 implies
+ *       around a validation round: the keys/values of the gamma+1 verification
+ *       positions become the last gamma+1 tokens of the cache before the target
+ *       runs; after n drafts are accepted the sequence has grown by n+1 tokens
+ *       (Alg. 1: "i <- j+1" per accepted draft, "i <- i+1" after the residual
+ *       draw), of which the last has no key/value yet, so the cache keeps the
+ *       first 1+n verification positions.
+ *
  * Pins: every function here is pinned by tests that do not call it to check
  * itself (dense torch attention on tiny inputs, closed forms, the eta = 0
  * reduction to textbook speculative sampling, chi-square against the
@@ -359,6 +367,55 @@ int oracle_chunk_stats(int rows, int64_t vocab, int64_t chunk, double T,
             cmax[r * nch + c] = m;
             csum[r * nch + c] = s;
         }
+    }
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ */
+/* Cache bookkeeping around one validation round.                       */
+/*                                                                      */
+/* Append: row i (0 <= i <= gamma_b) of k_new/v_new [B, Qmax, Hkv, d]    */
+/* becomes token ctx_lens[b] - (gamma_b+1) + i of sequence b's cache     */
+/* (ctx_lens already counts the appended positions).  Nothing else is    */
+/* written.                                                              */
+int oracle_kv_append(int B, int Qmax, int Hkv, int d,
+                     const uint16_t* k_new, const uint16_t* v_new,
+                     const int32_t* ctx_lens, const int32_t* gammas, int gamma,
+                     const oracle_kv_layout* lay, const int32_t* page_table,
+                     uint16_t* k_cache, uint16_t* v_cache)
+{
+    if (B < 1 || Qmax < 1 || Hkv < 1 || d < 1 || !k_new || !v_new || !ctx_lens || !lay || !k_cache || !v_cache)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        const int g = gammas ? gammas[b] : gamma;
+        const int Q = g + 1;
+        if (g < 0 || Q > Qmax || ctx_lens[b] < Q) return -2;
+        for (int i = 0; i < Q; ++i) {
+            const int64_t tok = (int64_t)ctx_lens[b] - Q + i;
+            for (int h = 0; h < Hkv; ++h) {
+                const int64_t dst = kv_offset(lay, page_table, b, tok, h);
+                const int64_t src = (((int64_t)b * Qmax + i) * Hkv + h) * d;
+                for (int c = 0; c < d; ++c) {
+                    k_cache[dst + c] = k_new[src + c];
+                    v_cache[dst + c] = v_new[src + c];
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Commit: of the gamma_b+1 verification positions the cache keeps the    */
+/* committed token and the n_b accepted drafts:                           */
+/*     ctx_lens[b] <- ctx_lens[b] - (gamma_b + 1) + (1 + n_b)              */
+int oracle_kv_commit(int B, const int32_t* gammas, int gamma, const int32_t* n_accepted, int32_t* ctx_lens)
+{
+    if (B < 1 || !n_accepted || !ctx_lens) return -1;
+    for (int b = 0; b < B; ++b) {
+        const int g = gammas ? gammas[b] : gamma;
+        if (n_accepted[b] < 0 || n_accepted[b] > g || ctx_lens[b] < g + 1) return -2;
+        ctx_lens[b] = ctx_lens[b] - (g + 1) + (1 + n_accepted[b]);
     }
     return 0;
 }
