@@ -204,6 +204,32 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Cache bookkeeping around one validation round (implied by Alg. 1: the target scores
+ * [C; x_<j] for every drafted position j, and "i <- j+1" per accepted draft, "i <- i+1"
+ * after the residual draw).
+ *
+ * rapid_kv_append: row i (0 <= i <= gamma_b) of k_new / v_new becomes token
+ * ctx_lens[b] - (gamma_b+1) + i of sequence b's cache; ctx_lens already counts the
+ * appended positions, exactly as rapid_verify_attn expects them.  Rows i > gamma_b and
+ * every other cache element are left untouched.  Rotary embedding etc. are the caller's.
+ *   shape        the same struct as for rapid_verify_attn (layout, batch, q_max, gamma)
+ *   k_new, v_new bf16 [B, Qmax, Hkv, d], contiguous, 16-byte aligned
+ *   ctx_lens, gammas, page_table   device arrays as for rapid_verify_attn
+ *   k_cache, v_cache               written in place
+ *
+ * rapid_kv_commit: of the gamma_b+1 verification positions the cache keeps the committed
+ * token and the n_accepted[b] accepted drafts (the newly drawn token has no key/value yet):
+ *     ctx_lens[b] <- ctx_lens[b] - (gamma_b + 1) + (1 + n_accepted[b])
+ * in place, on the device (n_accepted is rapid_accept's output; values outside
+ * [0, gamma_b] are clamped).  gammas == NULL: `gamma` for every sequence.
+ */
+int rapid_kv_append(rapid_ctx* ctx, const rapid_attn_shape* shape, const void* k_new, const void* v_new,
+                    const int32_t* ctx_lens, const int32_t* gammas, const int32_t* page_table,
+                    void* k_cache, void* v_cache, void* stream);
+int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas, const int32_t* n_accepted,
+                    int32_t* ctx_lens, void* stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` bytes of device memory at
  * `buf` once, with the load path of rapid_verify_attn (HBM -> LDS, streaming hint)
  * and no arithmetic, so that a benchmark can time the read bandwidth this device

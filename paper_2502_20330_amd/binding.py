@@ -20,7 +20,8 @@ RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP = -
 EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
            "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
-           "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_hbm_read_probe"]
+           "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_kv_append", "rapid_kv_commit",
+           "rapid_hbm_read_probe"]
 
 
 class RapidError(RuntimeError):
@@ -84,6 +85,10 @@ def load_library() -> ctypes.CDLL:
     lib.rapid_lm_head.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_float,
                                   f32p, ctypes.c_int64, f32p, vp]
     lib.rapid_lm_head.restype = ctypes.c_int
+    lib.rapid_kv_append.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape), vp, vp, i32p, i32p, i32p, vp, vp, vp]
+    lib.rapid_kv_append.restype = ctypes.c_int
+    lib.rapid_kv_commit.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, i32p, i32p, i32p, vp]
+    lib.rapid_kv_commit.restype = ctypes.c_int
     lib.rapid_hbm_read_probe.argtypes = [ctypes.c_void_p, vp, ctypes.c_size_t, vp, vp]
     lib.rapid_hbm_read_probe.restype = ctypes.c_int
     _lib = lib
@@ -231,6 +236,32 @@ class Rapid:
                 _dptr(n_acc), _dptr(toks), _dptr(ratio), _dptr(ws), ws.numel(), _stream_ptr(self.device))
         _check(self.lib, rc, self._ctx)
         return n_acc, toks, ratio
+
+    # ------------------------------------------------------------------ cache bookkeeping
+    def rapid_kv_append(self, k_cache, v_cache, k_new, v_new, ctx_lens, gamma: Optional[int] = None, *, gammas=None,
+                        page_table=None, max_ctx: Optional[int] = None):
+        """Writes rows 0..gamma_b of k_new/v_new (bf16 [B,Qmax,Hkv,d]) into the caches in place as the last
+        gamma_b+1 tokens of every sequence (ctx_lens counts them).  Cache layout as for rapid_verify_attn."""
+        B, Qmax, Hkv, d = k_new.shape
+        assert k_new.is_contiguous() and v_new.is_contiguous() and v_new.shape == k_new.shape
+        assert k_new.dtype == torch.bfloat16 and k_cache.dtype == torch.bfloat16
+        q_like = k_new                                         # only sizes are read from it
+        ctx_max = max_ctx if max_ctx is not None else (k_cache.shape[1] if page_table is None else
+                                                       page_table.shape[1] * k_cache.shape[1])
+        shape = self.attn_shape(q_like, k_cache, ctx_max, gamma=gamma if gamma is not None else Qmax - 1,
+                                page_table=page_table)
+        rc = self.lib.rapid_kv_append(self._ctx, ctypes.byref(shape), _dptr(k_new), _dptr(v_new), _dptr(ctx_lens),
+                                      _dptr(gammas), _dptr(page_table), _dptr(k_cache), _dptr(v_cache),
+                                      _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+
+    def rapid_kv_commit(self, ctx_lens, n_accepted, gamma: int = 0, *, gammas=None):
+        """ctx_lens[b] <- ctx_lens[b] - (gamma_b+1) + 1 + n_accepted[b], in place on the device."""
+        assert ctx_lens.dtype == torch.int32 and n_accepted.dtype == torch.int32
+        rc = self.lib.rapid_kv_commit(self._ctx, ctx_lens.numel(), int(gamma), _dptr(gammas), _dptr(n_accepted),
+                                      _dptr(ctx_lens), _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return ctx_lens
 
     # ------------------------------------------------------------------ output head
     def rapid_lm_head(self, h, w, *, temperature: float = 1.0, want_stats: bool = True, logits=None, stats=None):

@@ -287,6 +287,56 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
     return RAPID_OK;
 }
 
+int rapid_kv_append(rapid_ctx* ctx, const rapid_attn_shape* shape, const void* k_new, const void* v_new,
+                    const int32_t* ctx_lens, const int32_t* gammas, const int32_t* page_table,
+                    void* k_cache, void* v_cache, void* stream)
+{
+    if (!ctx) return RAPID_EINVAL;
+    int rc = check_attn_shape(shape);
+    if (rc != RAPID_OK) return rc;
+    if (!k_new || !v_new || !ctx_lens || !k_cache || !v_cache) return RAPID_EINVAL;
+    if (shape->page_size != 0 && !page_table) return RAPID_EINVAL;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16)) return RAPID_EALIGN;
+    KvAppendLaunch a{};
+    a.k_new = static_cast<const uint16_t*>(k_new);
+    a.v_new = static_cast<const uint16_t*>(v_new);
+    a.ctx_lens = ctx_lens;
+    a.gammas = gammas;
+    a.page_table = shape->page_size ? page_table : nullptr;
+    a.k_cache = static_cast<uint16_t*>(k_cache);
+    a.v_cache = static_cast<uint16_t*>(v_cache);
+    a.B = shape->batch;
+    a.Qmax = shape->q_max;
+    a.Hkv = shape->n_kv_heads;
+    a.D = shape->head_dim;
+    a.gamma = shape->gamma;
+    a.bstride = shape->kv_batch_stride;
+    a.tstride = shape->kv_token_stride;
+    a.hstride = shape->kv_head_stride;
+    a.pstride = shape->kv_page_stride;
+    a.max_pages = shape->max_pages;
+    a.page_shift = -1;
+    a.page_mask = 0;
+    if (shape->page_size) {
+        int sh = 0;
+        while ((1 << sh) < shape->page_size) ++sh;
+        a.page_shift = sh;
+        a.page_mask = shape->page_size - 1;
+    }
+    hipError_t e = launch_kv_append(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
+int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas, const int32_t* n_accepted,
+                    int32_t* ctx_lens, void* stream)
+{
+    if (!ctx || batch < 1 || gamma < 0 || !n_accepted || !ctx_lens) return RAPID_EINVAL;
+    hipError_t e = launch_kv_commit(batch, gamma, gammas, n_accepted, ctx_lens, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
 int rapid_hbm_read_probe(rapid_ctx* ctx, const void* buf, size_t bytes, void* sink, void* stream)
 {
     if (!ctx || !buf) return RAPID_EINVAL;

@@ -70,3 +70,20 @@ struct LmHeadLaunch {
     float inv_T;
 };
 hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream);
+
+// ---- cache bookkeeping (kv_cache.hip)
+struct KvAppendLaunch {
+    const uint16_t* k_new;      // [B][Qmax][Hkv][D]
+    const uint16_t* v_new;
+    const int32_t* ctx_lens;
+    const int32_t* gammas;
+    const int32_t* page_table;
+    uint16_t* k_cache;
+    uint16_t* v_cache;
+    int32_t B, Qmax, Hkv, D, gamma;
+    int64_t bstride, tstride, hstride, pstride;   // elements
+    int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
+};
+hipError_t launch_kv_append(const KvAppendLaunch& a, hipStream_t stream);
+hipError_t launch_kv_commit(int B, int gamma, const int32_t* gammas, const int32_t* n_accepted, int32_t* ctx_lens,
+                            hipStream_t stream);
