@@ -46,6 +46,7 @@ def _load():
         lib.oracle_distributions.restype = None
         lib.oracle_lm_head.restype = ctypes.c_int
         lib.oracle_kv_append.restype = ctypes.c_int
+        lib.oracle_retrieve.restype = ctypes.c_int
         lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_chunk_stats.restype = ctypes.c_int
         _lib = lib
@@ -231,3 +232,22 @@ def kv_commit(ctx_lens, n_accepted, *, gamma=None, gammas=None):
     if rc != 0:
         raise ValueError(f"oracle_kv_commit: invalid argument (rc={rc})")
     return out
+
+
+def retrieve(emb, query, top_k: int, threshold: float):
+    """Chunk selection: returns (sim float64 [n], selected int32 [count] in document order, margin)."""
+    lib = _load()
+    emb = np.ascontiguousarray(emb, dtype=np.float32)
+    query = np.ascontiguousarray(query, dtype=np.float32)
+    n, dim = emb.shape
+    sim = np.empty(n, dtype=np.float64)
+    sel = np.empty(max(top_k, 1), dtype=np.int32)
+    cnt = ctypes.c_int32(0)
+    mg = ctypes.c_double(0.0)
+    rc = lib.oracle_retrieve(ctypes.c_int(n), ctypes.c_int(dim), _ptr(emb, ctypes.c_float),
+                             _ptr(query, ctypes.c_float), ctypes.c_int(top_k), ctypes.c_double(threshold),
+                             _ptr(sim, ctypes.c_double), _ptr(sel, ctypes.c_int32), ctypes.byref(cnt),
+                             ctypes.byref(mg))
+    if rc != 0:
+        raise ValueError(f"oracle_retrieve: invalid argument (rc={rc})")
+    return sim, sel[:cnt.value].copy(), mg.value

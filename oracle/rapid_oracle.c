@@ -47,6 +47,12 @@
  *       draw), of which the last has no key/value yet, so the cache keeps the
  *       first 1+n verification positions.
  *
+ *   oracle_retrieve     -- chunk selection of the RAG drafter (Sec. 2.2; "RAG
+ *       Setup" in Sec. 3): cosine similarity of every chunk embedding with the
+ *       query embedding, the top-k chunks, those below the similarity threshold
+ *       dropped.  Output order (document order) and tie handling (lower index
+ *       first) are this build's conventions; the paper does not state them.
+ *
  * Pins: every function here is pinned by tests that do not call it to check
  * itself (dense torch attention on tiny inputs, closed forms, the eta = 0
  * reduction to textbook speculative sampling, chi-square against the
@@ -417,5 +423,50 @@ int oracle_kv_commit(int B, const int32_t* gammas, int gamma, const int32_t* n_a
         if (n_accepted[b] < 0 || n_accepted[b] > g || ctx_lens[b] < g + 1) return -2;
         ctx_lens[b] = ctx_lens[b] - (g + 1) + (1 + n_accepted[b]);
     }
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ */
+/* Retrieval: which chunks of the long context the drafter gets.        */
+/*   emb   float [n][dim] chunk embeddings, query float [dim]            */
+/*   sim[i] = <emb_i, query> / (|emb_i| |query|), 0 if either norm is 0  */
+/*   keep the top_k chunks by similarity (equal values: lower index      */
+/*   first), drop those with sim < threshold, report the rest in         */
+/*   ascending index order.  margin = smallest distance of any           */
+/*   similarity to a decision boundary (the k-th/k+1-th values and the   */
+/*   threshold): callers use it to recognise near-ties.                  */
+int oracle_retrieve(int n, int dim, const float* emb, const float* query, int top_k, double threshold,
+                    double* sim, int32_t* selected, int32_t* n_selected, double* margin)
+{
+    if (n < 1 || dim < 1 || top_k < 0 || !emb || !query || !sim || !selected || !n_selected) return -1;
+    double qn = 0.0;
+    for (int c = 0; c < dim; ++c) qn += (double)query[c] * (double)query[c];
+    qn = sqrt(qn);
+    for (int i = 0; i < n; ++i) {
+        double dot = 0.0, en = 0.0;
+        for (int c = 0; c < dim; ++c) {
+            dot += (double)emb[(int64_t)i * dim + c] * (double)query[c];
+            en += (double)emb[(int64_t)i * dim + c] * (double)emb[(int64_t)i * dim + c];
+        }
+        en = sqrt(en);
+        sim[i] = (en > 0.0 && qn > 0.0) ? dot / (en * qn) : 0.0;
+    }
+    /* rank of chunk i = number of chunks that come before it in the order   */
+    /* "larger similarity first, lower index first among equals"             */
+    int count = 0;
+    double mg = INFINITY, kth = -INFINITY, next = -INFINITY;
+    for (int i = 0; i < n; ++i) {
+        int rank = 0;
+        for (int j = 0; j < n; ++j)
+            if (sim[j] > sim[i] || (sim[j] == sim[i] && j < i)) ++rank;
+        if (rank == top_k - 1) kth = sim[i];
+        if (rank == top_k) next = sim[i];
+        if (rank < top_k && sim[i] >= threshold) selected[count++] = i;   /* i ascending: document order */
+        if (fabs(sim[i] - threshold) < mg) mg = fabs(sim[i] - threshold);
+    }
+    if (top_k >= 1 && top_k < n && kth - next < mg) mg = kth - next;
+    *n_selected = count;
+    if (margin) *margin = mg;
     return 0;
 }

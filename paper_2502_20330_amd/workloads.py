@@ -235,3 +235,29 @@ def gen_lm_head_inputs(rows: int, hidden: int, vocab: int, *, logit_std: float =
     h = _normal_bf16(rng, (rows, hidden))
     w = _normal_bf16(rng, (vocab, hidden), scale=logit_std / math.sqrt(hidden))
     return h, w
+
+
+# ---------------------------------------------------------------- retrieval
+SEED_RETRIEVAL = 6
+
+
+def retrieval_top_k(ctx_tokens: int, chunk_tokens: int = 512) -> int:
+    """Chunks the drafter's context may hold ("RAG Setup", Sec. 3): the retrieval context is at least 4096
+    tokens and otherwise 1/24 of the input, in whole chunks."""
+    return max(4096, ctx_tokens // 24) // chunk_tokens
+
+
+def gen_retrieval_inputs(n_chunks: int, dim: int = 1024, *, relevant: int = 12, salt: int = 0):
+    """Synthetic stand-in for sentence embeddings of the context's 512-token chunks and of the query (the
+    paper embeds with BGE-M3, dense dimension 1024; no model or text is available here): unit-scale Gaussian
+    chunk vectors, of which `relevant` share a component with the query so that their cosine similarities
+    spread over roughly 0.15..0.8 and straddle the 0.3 threshold; the rest sit near 0."""
+    rng = np.random.default_rng([SEED_RETRIEVAL, salt])
+    query = rng.standard_normal(dim).astype(np.float32)
+    emb = rng.standard_normal((n_chunks, dim)).astype(np.float32)
+    idx = rng.choice(n_chunks, size=min(relevant, n_chunks), replace=False)
+    mix = np.linspace(0.15, 0.8, num=len(idx)).astype(np.float32)
+    for i, a in zip(idx, mix):
+        emb[i] = a * query + np.sqrt(1.0 - a * a) * emb[i]
+    emb *= rng.uniform(0.5, 2.0, size=(n_chunks, 1)).astype(np.float32)      # norms vary: cosine, not dot
+    return emb, query

@@ -146,3 +146,12 @@ def test_llama_vocab_many_sequences():
     acc = wl.gen_accept_inputs(cfg, batch=64, salt=1)
     gpu, ref, st = check(cfg, acc, "V=128256 B=64")
     assert 0 < ref.n_accepted.mean() < acc.gammas.mean()        # both outcomes occur
+
+
+@pytest.mark.parametrize("eta,T", [(5.0, 1.0), (20.0, 1.0), (50.0, 1.0), (10.0, 0.1)])
+def test_paper_settings_gamma_10_llama_vocab(eta, T):
+    """gamma = 10 with the eta values the paper searches (5..20 self-speculation, 40..50 upward) and the low
+    temperature 0.1 of its robustness study, at the LLaMA vocabulary size, 8 sequences."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=8, gamma_choices=(10,), temperature=T, name=f"g10_eta{eta}_T{T}")
+    acc = wl.gen_accept_inputs(cfg)
+    check(cfg, acc, f"gamma=10 eta={eta} T={T}", eta=eta, temperature=T)

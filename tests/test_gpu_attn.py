@@ -77,7 +77,8 @@ def test_needle_key():
     assert np.abs(ref[0, 2, 13] - vf).max() < 0.1
 
 
-@pytest.mark.parametrize("hq,hkv,gam", [(64, 8, 8), (8, 8, 8), (16, 8, 4), (24, 8, 2), (8, 1, 9), (4, 4, 0)])
+@pytest.mark.parametrize("hq,hkv,gam", [(64, 8, 8), (8, 8, 8), (16, 8, 4), (24, 8, 2), (8, 1, 9), (4, 4, 0), (32, 8, 10),
+                                        (56, 8, 10)])
 def test_group_sizes_and_gammas(hq, hkv, gam):
     cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], n_q_heads=hq, n_kv_heads=hkv, gamma_choices=(gam,),
                     ctx=(1300, 1300), name=f"g{hq // hkv}_gamma{gam}")
@@ -279,3 +280,12 @@ def test_drafter_decode_step_full_size(name):
         assert int(inp.seqs.gammas.max()) == 0
         check(cfg, inp, what=f"{name}[layer {layer}]")
         check(cfg, inp, what=f"{name}[layer {layer}, head-major]", head_major=True)
+
+
+def test_paper_gamma_10_at_32k():
+    """The paper's own setting of gamma = 10 drafts per round (Sec. 3, implementation details): 11 query
+    positions x 4 heads = 44 packed rows per kv head, LLaMA-3.1-8B shape at 32K tokens, both cache orders."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], gamma_choices=(10,), name="gamma10_32k")
+    inp = wl.gen_attn_inputs(cfg)
+    check(cfg, inp)
+    check(cfg, inp, head_major=True, what="gamma10_32k head-major")
