@@ -230,6 +230,26 @@ int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas,
                     int32_t* ctx_lens, void* stream);
 
 /*
+ * Chunk selection of the RAG drafter (Sec. 2.2; "RAG Setup" in Sec. 3): the long context is
+ * cut into chunks, every chunk and the query are embedded by the caller, and the drafter's
+ * context is made of the top_k chunks by cosine similarity with the query, without those whose
+ * similarity is below `threshold` (the paper uses 512-token chunks and 0.3):
+ *     similarity[i] = <e_i, q> / (|e_i| |q|)      (0 if either norm is 0), fp32
+ *     selected      = { i : rank(i) < top_k and similarity[i] >= threshold }, ascending i,
+ * where rank orders by larger similarity first and lower index first among equal values (the
+ * order of the output and the tie rule are conventions of this library).
+ *
+ *   chunk_emb   fp32 [n_chunks, dim], contiguous, 16-byte aligned; n_chunks <= 1024, dim % 4 == 0
+ *   query_emb   fp32 [dim], 16-byte aligned
+ *   similarity  fp32 [n_chunks]
+ *   selected    int32 [top_k]: the kept chunk indices in document order, then -1
+ *   n_selected  int32 [1]
+ * All pointers are device memory.  No workspace.
+ */
+int rapid_retrieve(rapid_ctx* ctx, int n_chunks, int dim, const float* chunk_emb, const float* query_emb,
+                   int top_k, float threshold, float* similarity, int32_t* selected, int32_t* n_selected, void* stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` bytes of device memory at
  * `buf` once, with the load path of rapid_verify_attn (HBM -> LDS, streaming hint)
  * and no arithmetic, so that a benchmark can time the read bandwidth this device

@@ -21,7 +21,7 @@ EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_er
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
            "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
            "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_kv_append", "rapid_kv_commit",
-           "rapid_hbm_read_probe"]
+           "rapid_retrieve", "rapid_hbm_read_probe"]
 
 
 class RapidError(RuntimeError):
@@ -89,6 +89,9 @@ def load_library() -> ctypes.CDLL:
     lib.rapid_kv_append.restype = ctypes.c_int
     lib.rapid_kv_commit.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, i32p, i32p, i32p, vp]
     lib.rapid_kv_commit.restype = ctypes.c_int
+    lib.rapid_retrieve.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, f32p, f32p, ctypes.c_int, ctypes.c_float,
+                                   f32p, i32p, i32p, vp]
+    lib.rapid_retrieve.restype = ctypes.c_int
     lib.rapid_hbm_read_probe.argtypes = [ctypes.c_void_p, vp, ctypes.c_size_t, vp, vp]
     lib.rapid_hbm_read_probe.restype = ctypes.c_int
     _lib = lib
@@ -262,6 +265,21 @@ class Rapid:
                                       _dptr(ctx_lens), _stream_ptr(self.device))
         _check(self.lib, rc, self._ctx)
         return ctx_lens
+
+    # ------------------------------------------------------------------ retrieval
+    def rapid_retrieve(self, chunk_emb, query_emb, top_k: int, threshold: float = 0.3):
+        """chunk_emb fp32 [n, dim], query_emb fp32 [dim] -> (similarity fp32 [n], selected int32 [top_k]
+        (document order, then -1), n_selected int32 [1]); all on the device."""
+        n, dim = chunk_emb.shape
+        assert chunk_emb.dtype == torch.float32 and chunk_emb.is_contiguous()
+        assert query_emb.dtype == torch.float32 and query_emb.is_contiguous() and query_emb.shape == (dim,)
+        sim = torch.empty(n, dtype=torch.float32, device=self.device)
+        sel = torch.empty(max(int(top_k), 1), dtype=torch.int32, device=self.device)
+        cnt = torch.empty(1, dtype=torch.int32, device=self.device)
+        rc = self.lib.rapid_retrieve(self._ctx, n, dim, _dptr(chunk_emb), _dptr(query_emb), int(top_k),
+                                     float(threshold), _dptr(sim), _dptr(sel), _dptr(cnt), _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return sim, sel, cnt
 
     # ------------------------------------------------------------------ output head
     def rapid_lm_head(self, h, w, *, temperature: float = 1.0, want_stats: bool = True, logits=None, stats=None):

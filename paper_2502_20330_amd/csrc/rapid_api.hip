@@ -337,6 +337,28 @@ int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas,
     return RAPID_OK;
 }
 
+int rapid_retrieve(rapid_ctx* ctx, int n_chunks, int dim, const float* chunk_emb, const float* query_emb,
+                   int top_k, float threshold, float* similarity, int32_t* selected, int32_t* n_selected, void* stream)
+{
+    if (!ctx || !chunk_emb || !query_emb || !similarity || !selected || !n_selected) return RAPID_EINVAL;
+    if (n_chunks < 1 || dim < 1 || top_k < 1 || !(threshold == threshold)) return RAPID_EINVAL;
+    if (n_chunks > 1024 || dim % 4) return RAPID_EUNSUPPORTED;
+    if (!aligned(chunk_emb, 16) || !aligned(query_emb, 16)) return RAPID_EALIGN;
+    RetrieveLaunch a{};
+    a.emb = chunk_emb;
+    a.query = query_emb;
+    a.sim = similarity;
+    a.selected = selected;
+    a.n_selected = n_selected;
+    a.n = n_chunks;
+    a.dim = dim;
+    a.top_k = top_k;
+    a.threshold = threshold;
+    hipError_t e = launch_retrieve(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
 int rapid_hbm_read_probe(rapid_ctx* ctx, const void* buf, size_t bytes, void* sink, void* stream)
 {
     if (!ctx || !buf) return RAPID_EINVAL;

@@ -87,3 +87,15 @@ struct KvAppendLaunch {
 hipError_t launch_kv_append(const KvAppendLaunch& a, hipStream_t stream);
 hipError_t launch_kv_commit(int B, int gamma, const int32_t* gammas, const int32_t* n_accepted, int32_t* ctx_lens,
                             hipStream_t stream);
+
+// ---- retrieval chunk selection (retrieve.hip)
+struct RetrieveLaunch {
+    const float* emb;       // [n][dim]
+    const float* query;     // [dim]
+    float* sim;             // [n]
+    int32_t* selected;      // [top_k], unused tail = -1
+    int32_t* n_selected;    // [1]
+    int32_t n, dim, top_k;
+    float threshold;
+};
+hipError_t launch_retrieve(const RetrieveLaunch& a, hipStream_t stream);
