@@ -155,3 +155,23 @@ def test_paper_settings_gamma_10_llama_vocab(eta, T):
     cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=8, gamma_choices=(10,), temperature=T, name=f"g10_eta{eta}_T{T}")
     acc = wl.gen_accept_inputs(cfg)
     check(cfg, acc, f"gamma=10 eta={eta} T={T}", eta=eta, temperature=T)
+
+
+def test_nan_and_inf_logits_do_not_hang_or_write_out_of_range():
+    """Behaviour on NaN / infinite logits is unspecified, but every call must return and every emitted
+    token must be a vocabulary index or -1."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=5000, gamma_choices=(3,))
+    acc = wl.gen_accept_inputs(cfg, batch=6)
+    zt, zd = acc.target_logits.copy(), acc.draft_logits.copy()
+    zt[0, 1, 17] = np.nan
+    zd[1, 0, :] = np.nan
+    zt[2, :, :] = np.nan
+    zt[3, 2, 99] = np.inf
+    zd[4, 1, 5] = -np.inf
+    zt[5, :, :] = -np.inf
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    n, tok, _ = gu.rapid().rapid_accept(dev(zt), dev(zd), dev(acc.draft_tokens), 1.0, dev(acc.uniforms))
+    torch.cuda.synchronize()
+    n, tok = n.cpu().numpy(), tok.cpu().numpy()
+    assert np.all((n >= 0) & (n <= 3))
+    assert np.all((tok >= -1) & (tok < cfg.vocab))

@@ -201,24 +201,14 @@ def test_llama8b_128k_layers_full_size():
         check(cfg, inp, what=f"{cfg.name}[layer {layer}]")
 
 
-def test_llama8b_128k_head_major_full_size():
-    """Config 3 shape with the cache in [B, Hkv, L, d] memory order (the layout the benchmark
-    times by default): same data, strides only; every output element against the oracle."""
+@pytest.mark.parametrize("layer", [0, 10, 21, 31])
+def test_llama8b_128k_head_major_full_size(layer):
+    """Config 3 shape with the cache in [B, Hkv, L, d] memory order, exactly the launch configuration the
+    benchmark times by default (one workgroup per compute unit, rotated heads, uneven split pairs): four of
+    the 32 layers including the first and the last, every output element against the oracle."""
     cfg = wl.CONFIGS["llama8b_128k_step"]
-    inp = wl.gen_attn_inputs(cfg, layer=1)
-    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
-    kh = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
-    vh = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
-    del k, v
-    ctx = torch.from_numpy(inp.seqs.ctx_lens).cuda()
-    out = gu.rapid().rapid_verify_attn(q, kh, vh, ctx, softmax_scale=cfg.softmax_scale)
-    torch.cuda.synchronize()
-    import oracle
-    bs, ts, hs, ps = wl.kv_strides(cfg, inp.seqs)
-    ref = oracle.verify_attn(inp.q, inp.k, inp.v, inp.seqs.ctx_lens, oracle.KVLayout(bs, ts, hs),
-                             Hkv=cfg.n_kv_heads, scale=cfg.softmax_scale, gammas=inp.seqs.gammas)
-    e_abs, e_rel = gu.assert_attn_close(gu.bf16_to_host(out), ref, "head-major 128k")
-    print(f"[head-major 128k] max_abs={e_abs:.3e} max_rel={e_rel:.3e}")
+    inp = wl.gen_attn_inputs(cfg, layer=layer)
+    check(cfg, inp, what=f"{cfg.name}[layer {layer}, head-major]", head_major=True)
 
 
 def test_ragged_paged_full_size():
