@@ -251,3 +251,9 @@ def retrieve(emb, query, top_k: int, threshold: float):
     if rc != 0:
         raise ValueError(f"oracle_retrieve: invalid argument (rc={rc})")
     return sim, sel[:cnt.value].copy(), mg.value
+
+
+def retrieval_top_k(ctx_tokens: int, chunk_tokens: int = 512) -> int:
+    """Chunks the drafter's context may hold ("RAG Setup", Sec. 3): the retrieval context is at least 4096
+    tokens and otherwise 1/24 of the input, counted in whole chunks."""
+    return max(4096, ctx_tokens // 24) // chunk_tokens

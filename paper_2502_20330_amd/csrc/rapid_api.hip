@@ -35,6 +35,8 @@ int check_attn_shape(const rapid_attn_shape* s)
     // rows of one (sequence, head) are addressed with 32-bit byte offsets
     const int64_t span_tokens = s->page_size ? s->page_size : s->max_ctx;
     if (s->kv_token_stride * 2 * span_tokens >= (int64_t)1 << 32) return RAPID_EUNSUPPORTED;
+    // and so are the rows of q
+    if ((int64_t)s->batch * s->q_max * s->n_q_heads * s->head_dim * 2 >= (int64_t)1 << 32) return RAPID_EUNSUPPORTED;
     return RAPID_OK;
 }
 

@@ -58,7 +58,7 @@ struct Geo {
 template <int D, int RB>
 constexpr int attn_lds_bytes()
 {
-    constexpr int tiles = kWaves * Geo<D>::WAVE_LDS;
+    constexpr int tiles = kWaves * Geo<D>::WAVE_LDS + RB * 16 * Geo<D>::ROWB;   // rings + the Q block
     constexpr int merge = (2 * RB * 16 * (D + 4) + kWaves * RB * 16 * 2) * 4;
     return tiles > merge ? tiles : merge;
 }
@@ -115,6 +115,14 @@ __device__ __forceinline__ RowAddr make_row_addr(const AttnLaunch& a, int b, int
 __device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+// The same load without the streaming hint, for data that other workgroups read again (Q).
+__device__ __forceinline__ void dma16_keep(const char* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(byte_off), "s"(base), "s"(lds_addr)
                  : "memory", "m0");
@@ -326,41 +334,57 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     const uint32_t kring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * G::WAVE_LDS;
     const uint32_t vring_lds = kring_lds + 2 * G::SLOT;
 
+    // Q block of this kv head: RP rows of D bf16, HBM -> LDS once per workgroup, each wave
+    // fetching a share.  These loads are issued BEFORE the first K/V tiles: loads return in
+    // order, so Q is complete as soon as only the tile loads are still outstanding, and the
+    // math can start on tile 0 while tile 1 is still in flight.  (Waiting for everything
+    // here would let all 1024 waves of the grid drain the memory pipeline at the same
+    // moment, right after the start.)  Rows past the real ones repeat a valid row and are
+    // zeroed when read.
+    char* qlds = smem + kWaves * G::WAVE_LDS;
+    {
+        const uint32_t q_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + kWaves * G::WAVE_LDS;
+        constexpr int QI = RP / G::RPI;                  // 1 KiB loads that make up the block
+        const int last_row = a.Qmax * a.G - 1;
+        for (int e = wave; e < QI; e += kWaves) {
+            const int row = e * G::RPI + lane / G::CPR;
+            const int rr = min(row, last_row);
+            const int qi = rr / a.G, qg = rr % a.G;
+            const int c = (lane % G::CPR) ^ k_swz(row);
+            const uint32_t off = (uint32_t)(((((int64_t)b * a.Qmax + qi) * a.Hq + hkv * a.G + qg) * D) * 2) + c * 16;
+            dma16_keep(reinterpret_cast<const char*>(a.q), off, q_lds + e * 1024);
+        }
+    }
+
     // Start the pipeline: tiles 0 and 1 of this wave.
     if (nt > 0) {
         dma_tile<D, PAGED, false>(addr, kring_lds, tile_t0(0), last_tok, lane);
         dma_tile<D, PAGED, true>(addr, vring_lds, tile_t0(0), last_tok, lane);
         dma_tile<D, PAGED, false>(addr, kring_lds + G::SLOT, tile_t0(1), last_tok, lane);
         dma_tile<D, PAGED, true>(addr, vring_lds + G::SLOT, tile_t0(1), last_tok, lane);
+        wait_loads<4 * G::NLD>();                       // everything older than the four tiles: Q
+    } else {
+        wait_loads<0>();
     }
-
+    __syncthreads();                                     // the whole Q block is in LDS
 
     // Q^T as the B operand of the score product, kept in registers for the whole split.
     bf16x8 qf[RB][G::KS];
     int lim[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        int row = rb * 16 + ln;
-        bool real = row < R;
-        int qi = real ? row / a.G : 0, qg = real ? row % a.G : 0;
+        const int row = rb * 16 + ln;
+        const bool real = row < R;
+        const int qi = real ? row / a.G : 0;
         lim[rb] = min(real ? L - Q + qi : L - 1, c1 - 1);   // last key this row may see in this split
-        const uint16_t* qrow = a.q + (((int64_t)b * a.Qmax + qi) * a.Hq + hkv * a.G + qg) * D;
 #pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
-            u32x4 raw = real ? *reinterpret_cast<const u32x4*>(qrow + ks * 32 + lg * 8) : u32x4{0, 0, 0, 0};
+            const int c = (ks * 4 + lg) ^ k_swz(row);
+            u32x4 raw = *reinterpret_cast<const u32x4*>(qlds + row * G::ROWB + c * 16);
+            if (!real) raw = u32x4{0, 0, 0, 0};
             qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
         }
     }
-    // Retire the Q loads here, once (this also lands tiles 0 and 1, which iteration 0
-    // needs anyway): a wait for them inside the loop would drain the ring every tile.
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int ks = 0; ks < G::KS; ++ks) {
-            u32x4 raw = __builtin_bit_cast(u32x4, qf[rb][ks]);
-            asm volatile("" : "+v"(raw));
-            qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
-        }
 
     WaveState<D, RB> st;
 #pragma unroll

@@ -241,12 +241,6 @@ def gen_lm_head_inputs(rows: int, hidden: int, vocab: int, *, logit_std: float =
 SEED_RETRIEVAL = 6
 
 
-def retrieval_top_k(ctx_tokens: int, chunk_tokens: int = 512) -> int:
-    """Chunks the drafter's context may hold ("RAG Setup", Sec. 3): the retrieval context is at least 4096
-    tokens and otherwise 1/24 of the input, in whole chunks."""
-    return max(4096, ctx_tokens // 24) // chunk_tokens
-
-
 def gen_retrieval_inputs(n_chunks: int, dim: int = 1024, *, relevant: int = 12, salt: int = 0):
     """Synthetic stand-in for sentence embeddings of the context's 512-token chunks and of the query (the
     paper embeds with BGE-M3, dense dimension 1024; no model or text is available here): unit-scale Gaussian

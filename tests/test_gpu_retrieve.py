@@ -46,7 +46,7 @@ def run(emb, q, k, thr, what):
 def test_paper_setting_128k_context():
     """256 chunks of 512 tokens (a 128K-token context), dimension 1024, k from the 1/24 rule, threshold 0.3."""
     emb, q = wl.gen_retrieval_inputs(256)
-    k = wl.retrieval_top_k(131072)
+    k = oracle.retrieval_top_k(131072)
     assert k == 10
     assert not run(emb, q, k, 0.3, "128k")
 

@@ -47,6 +47,6 @@ def test_scaling_a_chunk_does_not_change_its_similarity_and_zero_vectors_score_z
 
 
 def test_budget_rule():
-    assert wl.retrieval_top_k(131072) == 10             # 1/24 of 128K = 5461 tokens -> 10 whole chunks
-    assert wl.retrieval_top_k(32768) == 8               # floor of 4096 tokens
-    assert wl.retrieval_top_k(1 << 20) == 85
+    assert oracle.retrieval_top_k(131072) == 10             # 1/24 of 128K = 5461 tokens -> 10 whole chunks
+    assert oracle.retrieval_top_k(32768) == 8               # floor of 4096 tokens
+    assert oracle.retrieval_top_k(1 << 20) == 85
