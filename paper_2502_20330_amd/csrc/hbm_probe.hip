@@ -52,21 +52,16 @@ __global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, 
 
 }  // namespace
 
+hipError_t configure_hbm_read_probe()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(hbm_read_stream),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kWaves * 2 * kBlock);
+}
+
 hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream)
 {
-    constexpr int lds = kWaves * 2 * kBlock;
-    static bool configured[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 64 && !configured[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(hbm_read_stream),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured[dev] = true;
-    }
     const int64_t nblock = (int64_t)(bytes / kBlock);
-    hipLaunchKernelGGL(hbm_read_stream, dim3(ctx->n_cu), dim3(kWaves * 64), lds, stream,
+    hipLaunchKernelGGL(hbm_read_stream, dim3(ctx->n_cu), dim3(kWaves * 64), kWaves * 2 * kBlock, stream,
                        static_cast<const char*>(buf), nblock, sink);
     return hipGetLastError();
 }

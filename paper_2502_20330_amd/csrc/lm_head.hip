@@ -254,20 +254,15 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
 
 }  // namespace
 
+hipError_t configure_lm_head()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes());
+}
+
 hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
 {
-    constexpr int lds = lds_bytes();
-    static bool configured[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 64 && !configured[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured[dev] = true;
-    }
     const int nwg = (a.vocab + kVB - 1) / kVB;
-    hipLaunchKernelGGL(lm_head_stream, dim3(nwg), dim3(kWaves * 64), lds, stream, a);
+    hipLaunchKernelGGL(lm_head_stream, dim3(nwg), dim3(kWaves * 64), lds_bytes(), stream, a);
     return hipGetLastError();
 }

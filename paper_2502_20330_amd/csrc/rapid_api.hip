@@ -94,6 +94,17 @@ int rapid_create(rapid_ctx** out, int device)
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);
     if (e != hipSuccess) return RAPID_EHIP;
+    // Kernels that need more dynamic LDS than the default limit are configured here, once
+    // per context, on the context's device: no launch path changes function attributes, so
+    // every entry point may be recorded into a stream capture.
+    int prev = 0;
+    if ((e = hipGetDevice(&prev)) != hipSuccess) return RAPID_EHIP;
+    if ((e = hipSetDevice(device)) != hipSuccess) return RAPID_EHIP;
+    hipError_t ec = configure_verify_attn();
+    if (ec == hipSuccess) ec = configure_lm_head();
+    if (ec == hipSuccess) ec = configure_hbm_read_probe();
+    (void)hipSetDevice(prev);
+    if (ec != hipSuccess) return RAPID_EHIP;
     rapid_ctx* c = new (std::nothrow) rapid_ctx;
     if (!c) return RAPID_EINVAL;
     c->device = device;

@@ -31,6 +31,7 @@ struct AttnLaunch {
     float scale_log2e;
 };
 hipError_t launch_verify_attn(const AttnLaunch& a, hipStream_t stream);
+hipError_t configure_verify_attn();   // per device, before the first launch
 size_t attn_workspace_bytes(int B, int Hkv, int nsplit, int RB, int D);
 
 // ---- accept pass (accept.hip)
@@ -57,6 +58,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int gmax, int V);
 
 // ---- streaming-read probe (hbm_probe.hip)
+hipError_t configure_hbm_read_probe();
 hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 // ---- output head (lm_head.hip)
@@ -70,6 +72,7 @@ struct LmHeadLaunch {
     float inv_T;
 };
 hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream);
+hipError_t configure_lm_head();
 
 // ---- cache bookkeeping (kv_cache.hip)
 struct KvAppendLaunch {

@@ -578,19 +578,29 @@ template <int D, int RB, bool PAGED>
 hipError_t launch_split(const AttnLaunch& a, hipStream_t stream)
 {
     constexpr int lds = attn_lds_bytes<D, RB>();
-    static bool configured[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
     auto fn = verify_attn_split<D, RB, PAGED>;
-    if (dev < 64 && !configured[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured[dev] = true;
-    }
     dim3 grid(a.Hkv, a.nsplit, a.B), block(kWaves * 64);
     hipLaunchKernelGGL(fn, grid, block, lds, stream, a);
     return hipGetLastError();
+}
+
+// The split kernels use more dynamic LDS than the default limit allows; raise it once
+// per device, ahead of any launch (and so outside any stream capture).
+template <int D, int RB, bool PAGED>
+hipError_t configure_split()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(verify_attn_split<D, RB, PAGED>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes<D, RB>());
+}
+template <int D, bool PAGED>
+hipError_t configure_rb()
+{
+    hipError_t e;
+    if ((e = configure_split<D, 1, PAGED>()) != hipSuccess) return e;
+    if ((e = configure_split<D, 2, PAGED>()) != hipSuccess) return e;
+    if ((e = configure_split<D, 3, PAGED>()) != hipSuccess) return e;
+    if ((e = configure_split<D, 4, PAGED>()) != hipSuccess) return e;
+    return configure_split<D, 5, PAGED>();
 }
 
 template <int D, bool PAGED>
@@ -607,6 +617,15 @@ hipError_t dispatch_rb(const AttnLaunch& a, hipStream_t stream)
 }
 
 }  // namespace
+
+hipError_t configure_verify_attn()
+{
+    hipError_t e;
+    if ((e = configure_rb<128, false>()) != hipSuccess) return e;
+    if ((e = configure_rb<128, true>()) != hipSuccess) return e;
+    if ((e = configure_rb<64, false>()) != hipSuccess) return e;
+    return configure_rb<64, true>();
+}
 
 size_t attn_workspace_bytes(int B, int Hkv, int nsplit, int RB, int D)
 {
