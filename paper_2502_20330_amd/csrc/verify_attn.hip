@@ -18,7 +18,7 @@
 //    workgroup barrier.
 //  * The lane -> global-chunk assignment of those loads applies an XOR swizzle,
 //    so that the later LDS reads (128-bit rows for K, transposed 64-bit reads for
-//    V) are bank-conflict free without padding.
+//    V) spread over all 64 banks without padding.
 //  * Scores are produced transposed (S^T = K Q^T: tokens on M, query rows on N): a
 //    query row's running max/sum then lives in one lane column, so the online
 //    softmax needs two cross-lane steps per tile instead of a butterfly per row.
@@ -63,14 +63,18 @@ constexpr int attn_lds_bytes()
     return tiles > merge ? tiles : merge;
 }
 
-// LDS swizzles (16-byte chunk index within a row):
-//   K: chunk c of row r is stored at c ^ (r & 7)          -> 8 consecutive rows, same
-//      logical chunk, land in 8 different bank quads (ds_read_b128 operand loads);
-//   V: chunk c of row r is stored at c ^ 2*((r ^ (r>>2)) & 3) -> the four rows a
-//      transposed read gathers, and the rows of different 16-lane groups, spread
-//      over all banks.
-__device__ __forceinline__ int k_swz(int row) { return row & 7; }
-__device__ __forceinline__ int v_swz(int row) { return ((row ^ (row >> 2)) & 3) << 1; }
+// LDS swizzles (16-byte chunk index within a row).  The LDS of this chip serves 64 banks of
+// 4 bytes per cycle: 16 lanes of a 128-bit read, 32 lanes of a 64-bit read.  Rows are unpadded
+// (256 B at d = 128, 128 B at d = 64), so without a swizzle all rows of an operand read would
+// hit the same banks.
+//   K / Q (ds_read_b128: 16 consecutive rows, same logical chunk): chunk c of row r is stored at
+//      c ^ (r & 15) for 256-byte rows; 128-byte rows pair up per 256 bytes, so there the row
+//      pair index does the work: c ^ ((r >> 1) & 7).
+//   V (transposed 64-bit reads: 8 consecutive rows, each lane group of four reading 32 bytes):
+//      the 32-byte unit u = c / 2 of row r is stored at u ^ (r & 7), i.e. c ^ 2 (r & 7);
+//      128-byte rows: c ^ 2 ((r >> 1) & 3).
+template <int D> __device__ __forceinline__ int k_swz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D> __device__ __forceinline__ int v_swz(int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); }
 
 // Where the rows of this (sequence, kv head) start.  A wave-uniform base pointer
 // plus a 32-bit byte offset per lane (the host checks that a sequence, or a page,
@@ -137,7 +141,7 @@ __device__ __forceinline__ void dma_tile(const RowAddr& ra, uint32_t slot, int t
 #pragma unroll
     for (int e = 0; e < G::NLD; ++e) {
         const int row = e * G::RPI + r_local;
-        const int c = cpos ^ (IS_V ? v_swz(row) : k_swz(row));
+        const int c = cpos ^ (IS_V ? v_swz<D>(row) : k_swz<D>(row));
         const int tok = min(t0 + row, last_tok);
         if (PAGED) {
             // the RPI rows of one instruction lie in one page (pages hold >= 16 tokens)
@@ -184,7 +188,7 @@ __device__ __forceinline__ void score_tile(floatx4 (&s)[2][RB], const bf16x8 (&q
 #pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
             const int row = tb * 16 + ln;
-            const int c = (ks * 4 + lg) ^ k_swz(row);
+            const int c = (ks * 4 + lg) ^ k_swz<D>(row);
             bf16x8 ka = *reinterpret_cast<const bf16x8*>(kt + row * G::ROWB + c * 16);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
@@ -268,7 +272,7 @@ __device__ __forceinline__ void pv_tile(WaveState<D, RB>& st, const bf16x8 (&pb)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int row = h * 16 + lg * 4 + (ln >> 2);
-            const int c = (db * 2) ^ v_swz(row);                 // chunk pair of the 32-byte column unit
+            const int c = (db * 2) ^ v_swz<D>(row);                // chunk pair of the 32-byte column unit
             half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (s16x4 __attribute__((address_space(3)))*)(vt + row * G::ROWB + c * 16 + (ln & 3) * 8));
         }
@@ -350,7 +354,7 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
             const int row = e * G::RPI + lane / G::CPR;
             const int rr = min(row, last_row);
             const int qi = rr / a.G, qg = rr % a.G;
-            const int c = (lane % G::CPR) ^ k_swz(row);
+            const int c = (lane % G::CPR) ^ k_swz<D>(row);
             const uint32_t off = (uint32_t)(((((int64_t)b * a.Qmax + qi) * a.Hq + hkv * a.G + qg) * D) * 2) + c * 16;
             dma16_keep(reinterpret_cast<const char*>(a.q), off, q_lds + e * 1024);
         }
@@ -379,7 +383,7 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
         lim[rb] = min(real ? L - Q + qi : L - 1, c1 - 1);   // last key this row may see in this split
 #pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
-            const int c = (ks * 4 + lg) ^ k_swz(row);
+            const int c = (ks * 4 + lg) ^ k_swz<D>(row);
             u32x4 raw = *reinterpret_cast<const u32x4*>(qlds + row * G::ROWB + c * 16);
             if (!real) raw = u32x4{0, 0, 0, 0};
             qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);

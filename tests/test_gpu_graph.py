@@ -40,9 +40,10 @@ def test_captured_round_replays_identically():
 
     out = torch.empty_like(q)
     lens = torch.empty_like(ctx)
-    outs = (torch.empty(cfg.batch, dtype=torch.int32, device="cuda"),
-            torch.empty(cfg.batch, cfg.q_max, dtype=torch.int32, device="cuda"),
-            torch.empty(cfg.batch, cfg.gamma_max, dtype=torch.float32, device="cuda"))
+    # zeros: ratio entries at positions k >= gamma_b are never written by the library
+    outs = (torch.zeros(cfg.batch, dtype=torch.int32, device="cuda"),
+            torch.zeros(cfg.batch, cfg.q_max, dtype=torch.int32, device="cuda"),
+            torch.zeros(cfg.batch, cfg.gamma_max, dtype=torch.float32, device="cuda"))
     logits = torch.empty(5, 3000, dtype=torch.float32, device="cuda")
     stats = torch.empty(5, 6, 2, dtype=torch.float32, device="cuda")
 
@@ -73,6 +74,7 @@ def test_captured_round_replays_identically():
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for a, b in zip((out, lens, logits, stats, *outs), want):
-            assert torch.equal(a, b), f"replay {rep} differs from the eager round"
+        for name, a, b in zip(("out", "lens", "logits", "stats", "n_accepted", "tokens", "ratio"),
+                              (out, lens, logits, stats, *outs), want):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager round"
         assert torch.isfinite(scratch)
