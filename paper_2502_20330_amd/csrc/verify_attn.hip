@@ -518,7 +518,6 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
     __shared__ float red[2][4];
     const int row = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
     const int d = threadIdx.x;
-    const int L = a.ctx_lens[b];
     const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
     const int R = Q * a.G, RP = a.RB * 16;
     const int qi = row / a.G, qg = row % a.G;
@@ -529,22 +528,34 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
         if (a.lse_out && d == 0) a.lse_out[((int64_t)b * a.Hq + h) * a.Qmax + qi] = 0.f;
         return;
     }
-    int ns = min(L / a.chunk + 2, a.nsplit);          // splits that hold a token of this sequence
-    while (ns > 0 && split_begin(a, ns - 1, hkv) >= L) --ns;
     const int64_t pbase = ((int64_t)b * a.Hkv + hkv) * a.nsplit * RP;
     float M = -INFINITY, den = 0.f, num = 0.f;
+    int ns = a.nsplit;                                 // refined below, once the length has arrived
     for (int s0 = 0; s0 < ns; s0 += SB) {
-        const int nb = min(SB, ns - s0);
+        // The loads of a block do not wait for the sequence length: every split slot of the
+        // workspace is addressable, and the slots of splits that hold no token (stale or
+        // never written) are discarded after the fact.  The length is one more dependent
+        // memory round trip that this way overlaps with the loads.
+        const int nsb = min(SB, a.nsplit - s0);
         const float* po = a.part_o + (pbase + (int64_t)s0 * RP + row) * D + d;
         float o[SB];
 #pragma unroll
-        for (int j = 0; j < SB; ++j) o[j] = j < nb ? po[(int64_t)j * RP * D] : 0.f;
+        for (int j = 0; j < SB; ++j) o[j] = j < nsb ? po[(int64_t)j * RP * D] : 0.f;
         float ms = -INFINITY, ls = 0.f;
-        if (d < nb) {
+        if (d < nsb) {
             const float* ml = a.part_ml + (pbase + (int64_t)(s0 + d) * RP + row) * 2;
             ms = ml[0];
             ls = ml[1];
         }
+        if (s0 == 0) {
+            const int L = a.ctx_lens[b];
+            ns = min(L / a.chunk + 2, a.nsplit);      // splits that hold a token of this sequence
+            while (ns > 0 && split_begin(a, ns - 1, hkv) >= L) --ns;
+        }
+        const int nb = min(SB, ns - s0);
+#pragma unroll
+        for (int j = 0; j < SB; ++j) o[j] = j < nb ? o[j] : 0.f;
+        if (d >= nb) { ms = -INFINITY; ls = 0.f; }
         float mb = ms;                                 // D >= 64 > SB: the first wave holds them all
 #pragma unroll
         for (int off = 16; off > 0; off >>= 1) mb = fmaxf(mb, __shfl_xor(mb, off));
