@@ -9,12 +9,16 @@
 // times, so the kernel is bound by streaming W (vocab x hidden bf16, about 1 GB for a
 // 128K vocabulary) from HBM.  Design:
 //
-//  * One workgroup owns 512 consecutive vocabulary rows (4 MiB of W at hidden = 4096).
+//  * One workgroup owns up to 512 consecutive vocabulary rows (4 MiB of W at hidden =
+//    4096); the host picks the row count (a multiple of 16) so that the grid fills the
+//    chip in whole rounds: 501 rows x 251 workgroups would leave a second round of 41
+//    workgroups that cannot saturate HBM, 304 rows x 501 workgroups does not.
 //    Its four waves split the hidden dimension in quarters: a wave reads 2*hidden/4
 //    contiguous bytes of every row, 512 B at a time.
 //  * W travels HBM -> LDS directly (global_load_lds_dwordx4, 1 KiB per instruction)
 //    in tiles of 16 rows x 256 k (8 KiB) through a four-slot ring per wave, three tiles
-//    ahead of the math; the wave counts its own outstanding loads, so the main loop has
+//    ahead of the math (16 rows x 128 k, eight slots, seven ahead when the hidden size
+//    is a multiple of 512 only); the wave counts its own outstanding loads, so the main loop has
 //    no workgroup barrier.
 //  * The matching 256-k slab of h (16 rows, rows past the last real one repeat it)
 //    comes through the same ring as one more tile at the head of every slab and is
@@ -35,14 +39,22 @@ namespace {
 constexpr int kWaves = 4;
 constexpr int kNB = 32;                      // 16-row vocabulary blocks per workgroup
 constexpr int kVB = kNB * 16;                // vocabulary rows per workgroup (= statistics chunk)
-constexpr int kSlabK = 256;                  // hidden elements per tile row
-constexpr int kTileBytes = 16 * kSlabK * 2;  // 8 KiB
-constexpr int kSlots = 4;
-constexpr int kRing = kSlots * kTileBytes;   // per wave
+constexpr int kRing = 32768;                 // LDS ring per wave
+// Tile geometry for a slab width of SK hidden elements (256, or 128 for hidden sizes
+// that are a multiple of 512 but not of 1024, e.g. 3584).
+template <int SK>
+struct Tile {
+    static constexpr int BYTES = 16 * SK * 2;          // 8 KiB / 4 KiB
+    static constexpr int NLD = BYTES / 1024;           // 1 KiB load instructions per tile
+    static constexpr int RPI = 1024 / (SK * 2);        // rows moved by one instruction
+    static constexpr int CPR = SK * 2 / 16;            // 16-byte chunks per row
+    static constexpr int KS = SK / 32;                 // MFMA k-steps per tile
+    static constexpr int SLOTS = kRing / BYTES;        // 4 / 8
+    static constexpr int AHEAD = SLOTS - 1;            // tiles requested ahead of the math
+};
 constexpr int kVBP = kVB + 4;                // padded row of the epilogue buffer (floats)
 constexpr float kLog2e = 1.4426950408889634f;
 
-static_assert(kVB == RAPID_LM_HEAD_CHUNK, "public chunk size and kernel tile disagree");
 
 constexpr int lds_bytes()
 {
@@ -86,39 +98,42 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+template <int SK>
 __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
 {
+    using T = Tile<SK>;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ln = lane & 15, lg = lane >> 4;
-    const int v0 = blockIdx.x * kVB;
+    const int nb = a.nb;                                 // 16-row blocks per workgroup (<= kNB)
+    const int v0 = blockIdx.x * nb * 16;
     const uint32_t row_bytes = (uint32_t)a.hidden * 2u;
     const int kq = wave * (a.hidden / kWaves);          // first hidden element of this wave's quarter
-    const int nslab = a.hidden / (kWaves * kSlabK);
+    const int nslab = a.hidden / (kWaves * SK);
     char* ring = smem + wave * kRing;
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * kRing;
 
-    // Per-lane byte offsets of the eight loads of a tile, relative to the tile's first
-    // row and first k: instruction e moves rows 2e and 2e+1; lane i writes LDS bytes
+    // Per-lane byte offsets of the loads of a tile, relative to the tile's first row and
+    // first k: instruction e moves RPI consecutive rows; lane i writes LDS bytes
     // [16 i, 16 i + 16) of that 1 KiB and fetches the chunk the swizzle assigns there.
-    uint32_t woff[8], hoff[8];
+    uint32_t woff[T::NLD], hoff[T::NLD];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int r = 2 * e + (lane >> 5);
-        const uint32_t c = (uint32_t)((lane & 31) ^ (r & 15)) * 16u;
+    for (int e = 0; e < T::NLD; ++e) {
+        const int r = T::RPI * e + lane / T::CPR;
+        const uint32_t c = (uint32_t)((lane % T::CPR) ^ (r & 15)) * 16u;
         woff[e] = (uint32_t)r * row_bytes + c;
         hoff[e] = (uint32_t)min(r, a.n_rows - 1) * row_bytes + c;
     }
 
     // tile j of slab s: j = 0 is the h slab, j = 1..kNB the W row blocks
     auto issue = [&](int s, int j, int slot) {
-        const int64_t kbyte = (int64_t)(kq + s * kSlabK) * 2;
-        const uint32_t dst = ring_lds + slot * kTileBytes;
+        const int64_t kbyte = (int64_t)(kq + s * SK) * 2;
+        const uint32_t dst = ring_lds + slot * T::BYTES;
         if (j == 0) {
             const char* base = reinterpret_cast<const char*>(a.h) + kbyte;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dma16_keep(base, hoff[e], dst + e * 1024);
+            for (int e = 0; e < T::NLD; ++e) dma16_keep(base, hoff[e], dst + e * 1024);
             return;
         }
         // A block that reaches past the vocabulary reads the last 16 rows instead: its
@@ -127,47 +142,53 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
         const int row0 = min(v0 + (j - 1) * 16, a.vocab - 16);
         const char* base = reinterpret_cast<const char*>(a.w) + (int64_t)row0 * row_bytes + kbyte;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dma16(base, woff[e], dst + e * 1024);
+        for (int e = 0; e < T::NLD; ++e) dma16(base, woff[e], dst + e * 1024);
     };
 
-    issue(0, 0, 0);
-    issue(0, 1, 1);
-    issue(0, 2, 2);
+    // The wave's tiles form one sequence: slab 0 (h tile, then nb W tiles), slab 1, ...
+    // (ps, pj) walks that sequence AHEAD tiles in front of the math; past the end it keeps
+    // re-requesting a cached h tile so that the count of outstanding loads stays uniform.
+    int ps = 0, pj = 0, pt = 0;                          // next tile to request: slab, index, linear number
+    auto request_next = [&]() {
+        const int sl = pt & (T::SLOTS - 1);
+        if (ps < nslab) issue(ps, pj, sl);
+        else issue(nslab - 1, 0, sl);
+        ++pt;
+        if (++pj > nb) { pj = 0; ++ps; }
+    };
+#pragma unroll
+    for (int j = 0; j < T::AHEAD; ++j) request_next();
 
     floatx4 acc[kNB];
 #pragma unroll
     for (int j = 0; j < kNB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    bf16x8 hreg[8];
-    // operand read: lane (ln, lg) takes row ln, chunk 4 ks + lg of the 32 chunks of a row
-    const int rd_row = ln * (kSlabK * 2);
+    bf16x8 hreg[T::KS];
+    // operand read: lane (ln, lg) takes row ln, chunk 4 ks + lg of the chunks of a row
+    const int rd_row = ln * (SK * 2);
     const int rd_swz = ln & 15;
 
+    int t = 0;                                           // linear number of the tile being consumed
     for (int s = 0; s < nslab; ++s) {
-        const int slot0 = (s * (kNB + 1)) & (kSlots - 1);
-        const bool more = s + 1 < nslab;
 #pragma unroll
         for (int j = 0; j <= kNB; ++j) {
-            wait_loads<16>();                                  // tile (s, j) has landed
-            // three tiles ahead, into the slot whose reads finished last iteration
-            {
-                const int jn = j + 3, sl = (slot0 + j + 3) & (kSlots - 1);
-                if (jn <= kNB) issue(s, jn, sl);
-                else if (more) issue(s + 1, jn - (kNB + 1), sl);
-                else issue(s, 0, sl);                          // nothing left: a cached h tile keeps the count
-            }
-            const char* tile = ring + ((slot0 + j) & (kSlots - 1)) * kTileBytes;
-            if (j == 0) {
+            if (j <= nb) {                                     // this workgroup's slabs have 1 + nb tiles
+                wait_loads<(T::AHEAD - 1) * T::NLD>();         // tile (s, j) has landed
+                request_next();                                // into the slot whose reads finished last iteration
+                const char* tile = ring + (t & (T::SLOTS - 1)) * T::BYTES;
+                ++t;
+                if (j == 0) {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    hreg[ks] = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
-            } else {
+                    for (int ks = 0; ks < T::KS; ++ks)
+                        hreg[ks] = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
+                } else {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    bf16x8 wa = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
-                    acc[j - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, hreg[ks], acc[j - 1], 0, 0, 0);
+                    for (int ks = 0; ks < T::KS; ++ks) {
+                        bf16x8 wa = *reinterpret_cast<const bf16x8*>(tile + rd_row + (((ks * 4 + lg) ^ rd_swz) * 16));
+                        acc[j - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, hreg[ks], acc[j - 1], 0, 0, 0);
+                    }
                 }
+                lds_reads_done();
             }
-            lds_reads_done();
         }
     }
     wait_loads<0>();
@@ -178,7 +199,7 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
     float* red = zbuf + kWaves * 16 * kVBP;                    // [2][kWaves][16]
 #pragma unroll
     for (int j = 0; j < kNB; ++j)
-        *reinterpret_cast<floatx4*>(zbuf + (wave * 16 + ln) * kVBP + j * 16 + lg * 4) = acc[j];
+        if (j < nb) *reinterpret_cast<floatx4*>(zbuf + (wave * 16 + ln) * kVBP + j * 16 + lg * 4) = acc[j];
     __syncthreads();
 
     constexpr int kPer = kVB / (kWaves * 64);                  // vocabulary entries per thread
@@ -199,7 +220,7 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
             for (int u = 0; u < kPer; ++u) {
                 const int vl = tid + u * (kWaves * 64);
                 float x = 0.f;
-                if (v0 + vl < a.vocab) {
+                if (vl < nb * 16 && v0 + vl < a.vocab) {
                     x = zbuf[(0 * 16 + n) * kVBP + col[u]];
 #pragma unroll
                     for (int w = 1; w < kWaves; ++w) x += zbuf[(w * 16 + n) * kVBP + col[u]];
@@ -229,7 +250,7 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
             float sacc = 0.f;
 #pragma unroll
             for (int u = 0; u < kPer; ++u)
-                if (v0 + tid + u * (kWaves * 64) < a.vocab)
+                if (tid + u * (kWaves * 64) < nb * 16 && v0 + tid + u * (kWaves * 64) < a.vocab)
                     sacc += __builtin_amdgcn_exp2f((z[n][u] - M) * a.inv_T * kLog2e);
             sm[n] = wave_sum(sacc);
         }
@@ -256,13 +277,21 @@ __global__ void __launch_bounds__(kWaves * 64) lm_head_stream(LmHeadLaunch a)
 
 hipError_t configure_lm_head()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream<256>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes());
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream<128>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes());
 }
 
 hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
 {
-    const int nwg = (a.vocab + kVB - 1) / kVB;
-    hipLaunchKernelGGL(lm_head_stream, dim3(nwg), dim3(kWaves * 64), lds_bytes(), stream, a);
+    const int nwg = (a.vocab + a.nb * 16 - 1) / (a.nb * 16);
+    if (a.hidden % 1024 == 0)
+        hipLaunchKernelGGL(lm_head_stream<256>, dim3(nwg), dim3(kWaves * 64), lds_bytes(), stream, a);
+    else if (a.hidden % 512 == 0)
+        hipLaunchKernelGGL(lm_head_stream<128>, dim3(nwg), dim3(kWaves * 64), lds_bytes(), stream, a);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }

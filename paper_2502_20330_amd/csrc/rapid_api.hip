@@ -272,9 +272,29 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                                  n_accepted, out_tokens, accept_ratio, workspace, workspace_bytes, stream);
 }
 
-int rapid_lm_head_stat_chunks(int vocab)
+// Vocabulary rows per workgroup of the output head: the grid should fill the chip in whole
+// rounds (one workgroup per compute unit and round), with at most 512 rows per workgroup.
+static int lm_head_blocks(const rapid_ctx* ctx, int vocab)
 {
-    return vocab < 1 ? 0 : (vocab + RAPID_LM_HEAD_CHUNK - 1) / RAPID_LM_HEAD_CHUNK;
+    const int64_t blocks = ((int64_t)vocab + 15) / 16;
+    const int64_t n_cu = ctx ? ctx->n_cu : 256;
+    const int64_t rounds = (blocks + 32 * n_cu - 1) / (32 * n_cu);
+    int64_t nb = (blocks + rounds * n_cu - 1) / (rounds * n_cu);
+    if (nb < 1) nb = 1;
+    if (nb > 32) nb = 32;
+    return (int)nb;
+}
+
+int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab)
+{
+    return vocab < 1 ? 0 : 16 * lm_head_blocks(ctx, vocab);
+}
+
+int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab)
+{
+    if (vocab < 1) return 0;
+    const int chunk = 16 * lm_head_blocks(ctx, vocab);
+    return (vocab + chunk - 1) / chunk;
 }
 
 int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
@@ -283,7 +303,7 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
 {
     if (!ctx || !h || !w || !logits) return RAPID_EINVAL;
     if (n_rows < 1 || hidden < 1 || vocab < 1 || logits_row_stride < vocab || !(temperature > 0.f)) return RAPID_EINVAL;
-    if (n_rows > 16 || hidden % 1024 || vocab < 16) return RAPID_EUNSUPPORTED;
+    if (n_rows > 16 || hidden % 512 || vocab < 16) return RAPID_EUNSUPPORTED;
     if (!aligned(h, 16) || !aligned(w, 16) || !aligned(logits, 4) || !aligned(stats, 8)) return RAPID_EALIGN;
     LmHeadLaunch a{};
     a.h = static_cast<const uint16_t*>(h);
@@ -294,6 +314,7 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
     a.hidden = hidden;
     a.vocab = vocab;
     a.ldz = logits_row_stride;
+    a.nb = lm_head_blocks(ctx, vocab);
     a.inv_T = (float)(1.0 / (double)temperature);
     hipError_t e = launch_lm_head(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);

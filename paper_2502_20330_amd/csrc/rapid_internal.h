@@ -66,8 +66,9 @@ struct LmHeadLaunch {
     const uint16_t* h;      // [n_rows][hidden] bf16
     const uint16_t* w;      // [vocab][hidden] bf16
     float* logits;          // [n_rows][ldz]
-    float* stats;           // [n_rows][ceil(vocab/512)][2] or null
+    float* stats;           // [n_rows][ceil(vocab / (16 nb))][2] or null
     int32_t n_rows, hidden, vocab;
+    int32_t nb;             // 16-row vocabulary blocks per workgroup, 1..32 (statistics chunk = 16 nb)
     int64_t ldz;
     float inv_T;
 };

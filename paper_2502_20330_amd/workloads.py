@@ -81,6 +81,10 @@ CONFIGS = {
     "llama70b_128k_step": VerifyConfig("llama70b_128k_step", 80, 1, 64, 8, 128, (131072, 131072),
                                        (8,), 128256, 0.5, 4.0, 1.0, k_scale=1.0 / math.sqrt(128),
                                        etas=(0.25, 0.5, 1.0), hidden=8192),
+    # the paper's other model family at its small size (Qwen2.5-7B shape: 28 layers, 28 query / 4 kv heads,
+    # width 3584, vocabulary 152064), gamma = 10 as in the paper's runs
+    "qwen7b_128k_step": VerifyConfig("qwen7b_128k_step", 28, 1, 28, 4, 128, (131072, 131072), (10,), 152064,
+                                     5.0, 4.0, 1.0, k_scale=1.0 / math.sqrt(128), hidden=3584),
     # next rows: the drafter's own decode step on the retrieved context (Sec. 2.2: the drafter works on
     # the shortened context, one position per step): the same two calls at gamma = 0, where the accept
     # call reduces to drawing the next token from softmax(z / T)

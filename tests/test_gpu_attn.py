@@ -78,7 +78,7 @@ def test_needle_key():
 
 
 @pytest.mark.parametrize("hq,hkv,gam", [(64, 8, 8), (8, 8, 8), (16, 8, 4), (24, 8, 2), (8, 1, 9), (4, 4, 0), (32, 8, 10),
-                                        (56, 8, 10)])
+                                        (56, 8, 10), (28, 4, 8), (28, 4, 10)])
 def test_group_sizes_and_gammas(hq, hkv, gam):
     cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], n_q_heads=hq, n_kv_heads=hkv, gamma_choices=(gam,),
                     ctx=(1300, 1300), name=f"g{hq // hkv}_gamma{gam}")
