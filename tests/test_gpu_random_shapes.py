@@ -1,0 +1,102 @@
+"""Seeded random sweeps over shapes, layouts and launch plans, each case against the oracle.  The cases
+are drawn once from a fixed seed, so a failure names a reproducible case."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_20330_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+gu = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    global gu
+    import gpu_util
+    gu = gpu_util
+    yield
+
+
+def _attn_cases(n=36):
+    rng = np.random.default_rng(2024)
+    out = []
+    for i in range(n):
+        d = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        gmax = int(rng.integers(0, 11))
+        g_hi = max(1, 80 // (gmax + 1))
+        group = int(rng.integers(1, min(8, g_hi) + 1))
+        batch = int(rng.choice([1, 1, 2, 3, 5]))
+        lo = int(rng.integers(gmax + 1, 400))
+        hi = lo + int(rng.integers(0, 6000))
+        paged = bool(rng.integers(0, 2))
+        page = int(rng.choice([16, 32, 128]))
+        chunk = int(rng.choice([0, 128, 256, 384, 1024, 2048, 4096]))
+        head_major = bool(rng.integers(0, 2)) and not paged
+        gammas = tuple(sorted({gmax, int(rng.integers(0, gmax + 1))}))
+        out.append(dict(i=i, d=d, hkv=hkv, group=group, batch=batch, ctx=(lo, hi), paged=paged, page=page,
+                        chunk=chunk, head_major=head_major, gammas=gammas))
+    return out
+
+
+@pytest.mark.parametrize("c", _attn_cases(), ids=lambda c: f"attn{c['i']}")
+def test_random_attention_case(c):
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], name=f"rand{c['i']}", batch=c["batch"], n_kv_heads=c["hkv"],
+                    n_q_heads=c["hkv"] * c["group"], head_dim=c["d"], ctx=c["ctx"], gamma_choices=c["gammas"],
+                    paged=c["paged"], page_size=c["page"], k_scale=1.0 if c["i"] % 3 == 0 else 1.0 / np.sqrt(c["d"]))
+    inp = wl.gen_attn_inputs(cfg, layer=c["i"])
+    got, ref, lse, ref_lse = gu.run_attn_case(cfg, inp, chunk_tokens=c["chunk"], head_major=c["head_major"])
+    gu.assert_attn_close(got, ref, str(c))
+    for b in range(cfg.batch):
+        Q = int(inp.seqs.gammas[b]) + 1
+        assert np.all(got[b, Q:] == 0.0), str(c)
+        np.testing.assert_allclose(lse[b, :, :Q], ref_lse[b, :, :Q], rtol=2e-3, atol=2e-3, err_msg=str(c))
+
+
+def _accept_cases(n=24):
+    rng = np.random.default_rng(77)
+    out = []
+    for i in range(n):
+        out.append(dict(i=i, V=int(rng.choice([7, 100, 4096, 4097, 20000, 65536, 128256])), batch=int(rng.integers(1, 9)),
+                        gmax=int(rng.integers(0, 11)), eta=float(rng.choice([0.0, 0.25, 1.0, 5.0, 20.0, 50.0])),
+                        T=float(rng.choice([0.1, 0.5, 1.0, 1.5])), alpha=float(rng.choice([0.0, 0.1, 0.3])),
+                        noise=float(rng.choice([0.3, 1.0, 2.0]))))
+    return out
+
+
+@pytest.mark.parametrize("c", _accept_cases(), ids=lambda c: f"accept{c['i']}")
+def test_random_accept_case(c):
+    gch = tuple(sorted({c["gmax"], c["gmax"] // 2}))
+    cfg = wl.scaled(wl.CONFIGS["tiny"], name=f"racc{c['i']}", batch=c["batch"], vocab=c["V"], gamma_choices=gch,
+                    eta=c["eta"], temperature=c["T"], tail_alpha=c["alpha"], draft_noise_std=c["noise"], logit_std=3.0)
+    acc = wl.gen_accept_inputs(cfg, salt=c["i"])
+    gpu, ref = gu.run_accept_case(acc, eta=c["eta"], temperature=c["T"], tail_alpha=c["alpha"])
+    st = gu.compare_accept(gpu, ref, acc.gammas, cfg.gamma_max)
+    assert st["n_mismatch"] == 0 and st["token_mismatch"] == 0, (c, st)
+    assert st["max_ratio_rel_err"] < 1e-4, (c, st)
+
+
+def _head_cases(n=14):
+    rng = np.random.default_rng(99)
+    return [dict(i=i, rows=int(rng.integers(1, 17)), hidden=int(rng.choice([512, 1024, 1536, 2048, 2560, 4096])),
+                 vocab=int(rng.integers(16, 40000)), T=float(rng.choice([0.1, 1.0, 2.0]))) for i in range(n)]
+
+
+@pytest.mark.parametrize("c", _head_cases(), ids=lambda c: f"head{c['i']}")
+def test_random_output_head_case(c):
+    h, w = wl.gen_lm_head_inputs(c["rows"], c["hidden"], c["vocab"], salt=100 + c["i"])
+    logits, stats = gu.rapid().rapid_lm_head(gu.bf16_to_dev(h), gu.bf16_to_dev(w), temperature=c["T"])
+    torch.cuda.synchronize()
+    z = logits.cpu().numpy().astype(np.float64)
+    ref = oracle.lm_head(h, w)
+    assert np.all(np.abs(z - ref) <= 5e-5 + 1e-5 * np.abs(ref)), c
+    ch = gu.rapid().lm_head_chunk(c["vocab"])
+    cmax, csum = oracle.chunk_stats(ref, ch, c["T"])
+    st = stats.cpu().numpy().astype(np.float64)
+    assert st.shape[:2] == cmax.shape, c
+    np.testing.assert_allclose(st[:, :, 0], cmax, atol=5e-5 + 1e-5 * np.abs(cmax).max(), err_msg=str(c))
+    np.testing.assert_allclose(st[:, :, 1], csum * np.exp((cmax - st[:, :, 0]) / c["T"]),
+                               rtol=2e-5 + 1e-4 / c["T"], err_msg=str(c))
