@@ -365,10 +365,11 @@ __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a,
     const int ch = blockIdx.x, b = blockIdx.y;
     const int g = a.gammas ? a.gammas[b] : a.gmax;
     const int n = first_reject(ws, b, a.gmax, g);
-    if (ch == 0 && threadIdx.x <= a.gmax) {
-        const int k = threadIdx.x;               // accepted drafts, then -1 (the draw fills slot n later)
-        a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
-        if (k == 0) a.n_accepted[b] = n;
+    if (ch == 0) {
+        // accepted drafts, then -1 (the draw fills slot n later)
+        for (int k = threadIdx.x; k <= a.gmax; k += kThreads)
+            a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
+        if (threadIdx.x == 0) a.n_accepted[b] = n;
     }
     RowCtx c = make_row_ctx(a, ws, b, n, g);
     // one partial sum per wave: a run of 256 consecutive entries (the fp64 exponentials make

@@ -22,6 +22,7 @@ int check_attn_shape(const rapid_attn_shape* s)
     if (!(s->softmax_scale > 0.f)) return RAPID_EINVAL;
     if (s->chunk_tokens < 0) return RAPID_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return RAPID_EUNSUPPORTED;
+    if (s->batch > 65535) return RAPID_EUNSUPPORTED;                       // grid z dimension
     const int G = s->n_q_heads / s->n_kv_heads;
     if ((int64_t)s->q_max * G > 80) return RAPID_EUNSUPPORTED;
     if (s->page_size != 0) {
@@ -228,6 +229,7 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     if (gamma_max > 0 && (!draft_logits || !draft_tokens)) return RAPID_EINVAL;
     if (!(eta >= 0.f) || !(temperature > 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
     if ((target_stats && target_chunks < 1) || (draft_stats && draft_chunks < 1)) return RAPID_EINVAL;
+    if (batch > 65535 || gamma_max > 32767) return RAPID_EUNSUPPORTED;      // grid y / z dimensions
     if (!aligned(target_logits, 4) || !aligned(draft_logits, 4)) return RAPID_EALIGN;
     if (!aligned(target_stats, 8) || !aligned(draft_stats, 8)) return RAPID_EALIGN;
     const size_t need = accept_workspace_bytes(batch, gamma_max, vocab);
