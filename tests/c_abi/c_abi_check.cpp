@@ -1,0 +1,211 @@
+// A torch-free caller of the C ABI: plain HIP allocations, the two hot-path entry points on a small ragged
+// paged batch, and the float64 C oracle on the same inputs.  It shows that the boundary is usable from any
+// language and that parity does not depend on the Python binding.  TEST CODE: it links the oracle.
+//
+// Inputs are seeded and synthetic (a splitmix64 generator with a Box-Muller transform, defined here).
+// Exit status 0 = every check passed; each check prints one line.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "rapid.h"
+
+extern "C" {
+typedef struct {
+    int64_t batch_stride, token_stride, head_stride;
+    int32_t page_size;
+    int64_t page_stride;
+    int32_t max_pages;
+} oracle_kv_layout;
+int oracle_verify_attn(int B, int Qmax, int Hq, int Hkv, int d, double scale, const uint16_t* q, const uint16_t* k,
+                       const uint16_t* v, const oracle_kv_layout* lay, const int32_t* page_table,
+                       const int32_t* ctx_lens, const int32_t* gammas, int gamma, double* out, double* lse);
+int oracle_accept(int B, int gmax, int64_t V, const float* target_logits, const float* draft_logits,
+                  const int32_t* draft_tokens, const int32_t* gammas, double eta, double T, double tail_alpha,
+                  const float* uniforms, int32_t* n_accepted, int32_t* out_tokens, double* ratio,
+                  double* accept_margin, double* draw_margin);
+}
+
+#define HIP_OK(x)                                                                          \
+    do {                                                                                   \
+        hipError_t e_ = (x);                                                               \
+        if (e_ != hipSuccess) {                                                            \
+            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);          \
+            return 2;                                                                      \
+        }                                                                                  \
+    } while (0)
+#define RAPID_OK_(x)                                                                       \
+    do {                                                                                   \
+        int s_ = (x);                                                                      \
+        if (s_ != RAPID_OK) {                                                              \
+            printf("librapid status %d (%s) at line %d\n", s_, rapid_strerror(s_), __LINE__); \
+            return 2;                                                                      \
+        }                                                                                  \
+    } while (0)
+
+static uint64_t g_state = 0x243F6A8885A308D3ull;
+static uint64_t next_u64()
+{
+    uint64_t z = (g_state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+static double next_uniform() { return (double)(next_u64() >> 11) * (1.0 / 9007199254740992.0); }
+static float next_normal()
+{
+    double u1 = next_uniform(), u2 = next_uniform();
+    if (u1 < 1e-300) u1 = 1e-300;
+    return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586 * u2));
+}
+static uint16_t to_bf16(float x)   // round to nearest, ties to even
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+static double from_bf16(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+template <typename T>
+static T* to_device(const std::vector<T>& h)
+{
+    T* d = nullptr;
+    if (hipMalloc(&d, h.size() * sizeof(T) + 16) != hipSuccess) return nullptr;
+    if (hipMemcpy(d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+    return d;
+}
+
+int main()
+{
+    int failures = 0;
+    rapid_ctx* ctx = nullptr;
+    RAPID_OK_(rapid_create(&ctx, 0));
+
+    // ---------------------------------------------------------------- attention: 3 sequences, paged cache
+    const int B = 3, Hq = 8, Hkv = 2, d = 128, Qmax = 5, page = 16, max_pages = 80;
+    const int32_t ctx_lens_h[B] = {1187, 40, 733}, gammas_h[B] = {4, 2, 3};
+    const int n_pages = B * max_pages;
+    std::vector<int32_t> pt(B * max_pages);
+    {   // a seeded permutation of the pool as page table
+        std::vector<int32_t> perm(n_pages);
+        for (int i = 0; i < n_pages; ++i) perm[i] = i;
+        for (int i = n_pages - 1; i > 0; --i) {
+            int j = (int)(next_u64() % (uint64_t)(i + 1));
+            int t = perm[i]; perm[i] = perm[j]; perm[j] = t;
+        }
+        for (int i = 0; i < B * max_pages; ++i) pt[i] = perm[i];
+    }
+    const size_t kv_elems = (size_t)n_pages * page * Hkv * d;
+    std::vector<uint16_t> k(kv_elems), v(kv_elems), q((size_t)B * Qmax * Hq * d);
+    for (auto& x : k) x = to_bf16(next_normal());        // unscaled keys: a peaked softmax
+    for (auto& x : v) x = to_bf16(next_normal());
+    for (auto& x : q) x = to_bf16(next_normal());
+    std::vector<int32_t> ctx_v(ctx_lens_h, ctx_lens_h + B), gam_v(gammas_h, gammas_h + B);
+
+    rapid_attn_shape sh;
+    memset(&sh, 0, sizeof sh);
+    sh.batch = B; sh.q_max = Qmax; sh.n_q_heads = Hq; sh.n_kv_heads = Hkv; sh.head_dim = d;
+    sh.max_ctx = page * max_pages; sh.gamma = Qmax - 1; sh.softmax_scale = 1.0f / sqrtf((float)d);
+    sh.kv_token_stride = (int64_t)Hkv * d; sh.kv_head_stride = d; sh.kv_page_stride = (int64_t)page * Hkv * d;
+    sh.page_size = page; sh.max_pages = max_pages; sh.chunk_tokens = 256;
+
+    uint16_t *dq = to_device(q), *dk = to_device(k), *dv = to_device(v);
+    int32_t *dctx = to_device(ctx_v), *dgam = to_device(gam_v), *dpt = to_device(pt);
+    if (!dq || !dk || !dv || !dctx || !dgam || !dpt) { printf("allocation failed\n"); return 2; }
+    uint16_t* dout = nullptr;
+    float* dlse = nullptr;
+    HIP_OK(hipMalloc(&dout, q.size() * 2));
+    HIP_OK(hipMalloc(&dlse, (size_t)B * Hq * Qmax * 4));
+    const size_t ws_bytes = rapid_verify_attn_workspace_bytes(ctx, &sh);
+    void* ws = nullptr;
+    HIP_OK(hipMalloc(&ws, ws_bytes + 256));
+    RAPID_OK_(rapid_verify_attn(ctx, &sh, dq, dk, dv, dctx, dgam, dpt, dout, dlse, ws, ws_bytes, nullptr));
+    HIP_OK(hipDeviceSynchronize());
+    std::vector<uint16_t> out(q.size());
+    HIP_OK(hipMemcpy(out.data(), dout, out.size() * 2, hipMemcpyDeviceToHost));
+
+    oracle_kv_layout lay = {0, sh.kv_token_stride, sh.kv_head_stride, page, sh.kv_page_stride, max_pages};
+    std::vector<double> ref(q.size()), ref_lse((size_t)B * Hq * Qmax);
+    if (oracle_verify_attn(B, Qmax, Hq, Hkv, d, sh.softmax_scale, q.data(), k.data(), v.data(), &lay, pt.data(),
+                           ctx_lens_h, gammas_h, 0, ref.data(), ref_lse.data()) != 0) {
+        printf("oracle_verify_attn rejected its arguments\n");
+        return 2;
+    }
+    double worst = 0.0;
+    size_t bad = 0;
+    for (size_t i = 0; i < ref.size(); ++i) {
+        const double g = from_bf16(out[i]), e = fabs(g - ref[i]);
+        if (!(e <= 2e-2 + 1e-2 * fabs(ref[i]))) ++bad;
+        if (e > worst) worst = e;
+    }
+    printf("attention: %zu outputs, max abs err %.3e, %zu outside 2e-2 + 1e-2|ref| -> %s\n", ref.size(), worst, bad,
+           bad ? "FAIL" : "ok");
+    failures += bad != 0;
+
+    // ---------------------------------------------------------------- accept: same batch, vocabulary 5003
+    const int V = 5003, gmax = Qmax - 1;
+    std::vector<float> zt((size_t)B * (gmax + 1) * V), zd((size_t)B * gmax * V), uni((size_t)B * (gmax + 1));
+    for (auto& x : zt) x = 3.0f * next_normal();
+    for (int b = 0; b < B; ++b)
+        for (int kk = 0; kk < gmax; ++kk)
+            for (int t = 0; t < V; ++t)
+                zd[((size_t)b * gmax + kk) * V + t] = zt[((size_t)b * (gmax + 1) + kk) * V + t] + 0.7f * next_normal();
+    for (auto& x : uni) x = (float)next_uniform() * 0.99999f;
+    std::vector<int32_t> tok((size_t)B * gmax);
+    for (int b = 0; b < B; ++b)
+        for (int kk = 0; kk < gmax; ++kk) {   // the drafter's greedy token: a likely candidate
+            const float* row = &zd[((size_t)b * gmax + kk) * V];
+            int best = 0;
+            for (int t = 1; t < V; ++t) if (row[t] > row[best]) best = t;
+            tok[(size_t)b * gmax + kk] = best;
+        }
+    float *dzt = to_device(zt), *dzd = to_device(zd), *duni = to_device(uni);
+    int32_t* dtok = to_device(tok);
+    int32_t *dn = nullptr, *dtoks = nullptr;
+    float* dratio = nullptr;
+    HIP_OK(hipMalloc(&dn, B * 4));
+    HIP_OK(hipMalloc(&dtoks, (size_t)B * (gmax + 1) * 4));
+    HIP_OK(hipMalloc(&dratio, (size_t)B * gmax * 4));
+    const size_t ws2_bytes = rapid_accept_workspace_bytes(ctx, B, gmax, V);
+    void* ws2 = nullptr;
+    HIP_OK(hipMalloc(&ws2, ws2_bytes + 256));
+    const float eta = 2.0f, T = 0.8f, alpha = 0.1f;
+    RAPID_OK_(rapid_accept(ctx, B, gmax, V, dzt, dzd, dtok, dgam, eta, T, alpha, duni, dn, dtoks, dratio, ws2,
+                           ws2_bytes, nullptr));
+    HIP_OK(hipDeviceSynchronize());
+    std::vector<int32_t> n_acc(B), toks((size_t)B * (gmax + 1));
+    HIP_OK(hipMemcpy(n_acc.data(), dn, B * 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(toks.data(), dtoks, toks.size() * 4, hipMemcpyDeviceToHost));
+    std::vector<int32_t> rn(B), rt((size_t)B * (gmax + 1));
+    std::vector<double> ratio((size_t)B * gmax), am((size_t)B * gmax), dm(B);
+    if (oracle_accept(B, gmax, V, zt.data(), zd.data(), tok.data(), gammas_h, (double)eta, (double)T, (double)alpha,
+                      uni.data(), rn.data(), rt.data(), ratio.data(), am.data(), dm.data()) != 0) {
+        printf("oracle_accept rejected its arguments\n");
+        return 2;
+    }
+    for (int b = 0; b < B; ++b) {
+        bool near = dm[b] <= 1e-5;
+        for (int kk = 0; kk < gammas_h[b]; ++kk) near = near || am[(size_t)b * gmax + kk] <= 1e-5;
+        const bool same = n_acc[b] == rn[b] &&
+                          memcmp(&toks[(size_t)b * (gmax + 1)], &rt[(size_t)b * (gmax + 1)], (gmax + 1) * 4) == 0;
+        printf("accept seq %d: gpu n=%d token=%d, oracle n=%d token=%d -> %s\n", b, n_acc[b],
+               toks[(size_t)b * (gmax + 1) + n_acc[b]], rn[b], rt[(size_t)b * (gmax + 1) + rn[b]],
+               same ? "ok" : (near ? "near-tie (exempt)" : "FAIL"));
+        failures += !(same || near);
+    }
+    rapid_destroy(ctx);
+    printf(failures ? "FAILED\n" : "PASSED\n");
+    return failures ? 1 : 0;
+}
