@@ -7,7 +7,9 @@ HBM) followed by one accept/resample pass over the full vocabulary.
 
 Default workload: the Llama-3-8B-shaped full verify step at 128K context,
 gamma = 8 (32 layers, 32 query / 8 kv heads, head_dim 128, vocabulary 128256),
-the configuration the headline metric is quoted on.  Prints ONE JSON line.
+the configuration the headline metric is quoted on.  Prints ONE JSON line:
+`value` is the effective KV GB/s of the whole step, `verify_step_us` its latency and
+`hbm_frac_of_peak` the fraction of the 8 TB/s HBM peak (the three parts of the metric).
 """
 from __future__ import annotations
 
@@ -248,7 +250,7 @@ def main():
     # the committed counter summary covers the default launch configuration only
     profiled = (cfg.name == "llama8b_128k_step" and head_major and not args.chunk_tokens and layers == cfg.layers)
     result = {
-        "metric": "verify-step effective KV GB/s at 128K ctx, gamma=8 (verify-step us in verify_step_us)",
+        "metric": "verify-step \u00b5s + effective KV GB/s (% HBM peak) at 128K ctx, gamma=8",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "verify_step_us": round(ms_per_step * 1e3, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
