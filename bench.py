@@ -154,7 +154,7 @@ def main():
 
     # ---------------------------------------------------------------- prepared C-ABI calls
     shape = r.attn_shape(qs[0], ks[0], seqs.max_ctx, page_table=page_table, softmax_scale=cfg.softmax_scale,
-                         chunk_tokens=args.chunk_tokens)
+                         chunk_tokens=args.chunk_tokens, ctx_sum_hint=int(seqs.ctx_lens.astype(np.int64).sum()))
     chunk = r.verify_attn_chunk(shape)
     ws_attn = lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape))
     ws_acc = lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V)

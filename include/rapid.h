@@ -78,6 +78,10 @@ typedef struct rapid_attn_shape {
     int32_t page_size;        /* 0 = contiguous cache, else a power of two >= 16               */
     int32_t max_pages;        /* row length of page_table                                      */
     int32_t chunk_tokens;     /* tokens per KV split; 0 = let the library choose               */
+    int32_t reserved;         /* set to 0                                                      */
+    int64_t ctx_sum_hint;     /* sum of ctx_lens[b] if the host knows it (a scheduler usually  */
+                              /* does), else 0: only used to size the KV splits of ragged      */
+                              /* batches; results never depend on it                           */
 } rapid_attn_shape;
 
 /* Tokens per KV split the library will use for `shape` (multiple of 128), and

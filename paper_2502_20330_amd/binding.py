@@ -38,7 +38,8 @@ class AttnShape(ctypes.Structure):
                 ("kv_batch_stride", ctypes.c_int64), ("kv_token_stride", ctypes.c_int64),
                 ("kv_head_stride", ctypes.c_int64), ("kv_page_stride", ctypes.c_int64),
                 ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
-                ("chunk_tokens", ctypes.c_int32)]
+                ("chunk_tokens", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("ctx_sum_hint", ctypes.c_int64)]
 
 
 _lib = None
@@ -148,7 +149,8 @@ class Rapid:
 
     # ------------------------------------------------------------------ attention
     def attn_shape(self, q, k_cache, ctx_max: int, *, gamma: Optional[int] = None, page_table=None,
-                   softmax_scale: Optional[float] = None, chunk_tokens: int = 0) -> AttnShape:
+                   softmax_scale: Optional[float] = None, chunk_tokens: int = 0,
+                   ctx_sum_hint: int = 0) -> AttnShape:
         B, Qmax, Hq, d = q.shape
         s = AttnShape()
         s.batch, s.q_max, s.n_q_heads, s.head_dim = B, Qmax, Hq, d
@@ -167,6 +169,8 @@ class Rapid:
             s.kv_batch_stride = 0
             s.page_size, s.max_pages = k_cache.shape[1], page_table.shape[1]
         s.chunk_tokens = int(chunk_tokens)
+        s.reserved = 0
+        s.ctx_sum_hint = int(ctx_sum_hint)
         return s
 
     def verify_attn_chunk(self, shape: AttnShape) -> int:
@@ -177,7 +181,8 @@ class Rapid:
 
     def rapid_verify_attn(self, q, k_cache, v_cache, ctx_lens, gamma: Optional[int] = None, *, gammas=None,
                           page_table=None, max_ctx: Optional[int] = None, softmax_scale: Optional[float] = None,
-                          chunk_tokens: int = 0, out=None, lse_out=None, shape: Optional[AttnShape] = None):
+                          chunk_tokens: int = 0, out=None, lse_out=None, shape: Optional[AttnShape] = None,
+                          ctx_sum_hint: int = 0):
         """q bf16 [B,Qmax,Hq,d]; k_cache/v_cache bf16 [B,Lmax,Hkv,d] (any batch/token/head strides)
         or paged [n_pages,page,Hkv,d] with page_table int32 [B,max_pages]; ctx_lens int32 [B]
         (device).  ``max_ctx`` is a host upper bound of ctx_lens (default: the cache capacity).
@@ -189,7 +194,8 @@ class Rapid:
             if max_ctx is None:
                 max_ctx = k_cache.shape[1] if page_table is None else page_table.shape[1] * k_cache.shape[1]
             shape = self.attn_shape(q, k_cache, max_ctx, gamma=gamma, page_table=page_table,
-                                    softmax_scale=softmax_scale, chunk_tokens=chunk_tokens)
+                                    softmax_scale=softmax_scale, chunk_tokens=chunk_tokens,
+                                    ctx_sum_hint=ctx_sum_hint)
         if out is None:
             out = torch.empty_like(q)
         need = self.lib.rapid_verify_attn_workspace_bytes(self._ctx, ctypes.byref(shape))

@@ -20,7 +20,7 @@ int check_attn_shape(const rapid_attn_shape* s)
     if (s->n_q_heads % s->n_kv_heads) return RAPID_EINVAL;
     if (s->gamma < 0 || s->gamma >= s->q_max || s->max_ctx < s->q_max) return RAPID_EINVAL;
     if (!(s->softmax_scale > 0.f)) return RAPID_EINVAL;
-    if (s->chunk_tokens < 0) return RAPID_EINVAL;
+    if (s->chunk_tokens < 0 || s->ctx_sum_hint < 0) return RAPID_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return RAPID_EUNSUPPORTED;
     if (s->batch > 65535) return RAPID_EUNSUPPORTED;                       // grid z dimension
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -41,23 +41,34 @@ int check_attn_shape(const rapid_attn_shape* s)
     return RAPID_OK;
 }
 
-// Tokens per KV split: a multiple of 128 chosen so that the grid has about four
-// workgroups per compute unit when every sequence is max_ctx long (ragged batches
-// then still balance), but never below 256 tokens (two tiles per wave): measured on
-// 4K..16K contexts, shorter splits lose more to the per-workgroup prologue and
-// epilogue than the extra workgroups gain.
+// Tokens per KV split, a multiple of 128, never below 256 (two tiles per wave).
+// Measured on uniform and ragged batches of 2..64 sequences: a workgroup costs about 8 us
+// besides its streaming time, so for sequences of equal length one workgroup per compute
+// unit (a single round of long splits) beats any finer grid by 5..15 %.  When the lengths
+// differ, a single round leaves compute units idle behind the short sequences; two rounds
+// let the dispatcher back-fill.  The host cannot see the lengths (device data), so it
+// plans for equal lengths unless the caller passes their sum: then the split is sized so
+// that the non-empty workgroups fill at most two rounds.
 int plan_chunk(const rapid_ctx* ctx, const rapid_attn_shape* s)
 {
     const int quantum = 128;
     if (s->chunk_tokens > 0) return (s->chunk_tokens + quantum - 1) / quantum * quantum;
-    const int n_cu = ctx ? ctx->n_cu : 256;
+    const int64_t n_cu = ctx ? ctx->n_cu : 256;
     const int64_t units = (int64_t)s->batch * s->n_kv_heads;
-    const int64_t target_wg = s->batch > 1 ? 4LL * n_cu : 1LL * n_cu;
-    int64_t splits = (target_wg + units - 1) / units;
-    if (splits < 1) splits = 1;
-    int64_t chunk = (s->max_ctx + splits - 1) / splits;
+    const int64_t full = (int64_t)s->batch * s->max_ctx;
+    const bool ragged = s->batch > 1 && s->ctx_sum_hint > 0 && s->ctx_sum_hint * 10 < full * 9;
+    const int64_t tokens = (s->ctx_sum_hint > 0 && s->ctx_sum_hint < full) ? s->ctx_sum_hint : full;
+    // workgroups that may hold tokens: every (sequence, head) wastes less than one split, so
+    // sum_b ceil(L_b / chunk) * Hkv <= tokens * Hkv / chunk + units stays within two full rounds
+    // (a third round of a few stragglers, each limited to one compute unit's bandwidth, is the
+    // worst case)
+    int64_t wgs = ragged ? 2 * n_cu - units : n_cu;
+    if (wgs < units) wgs = units;
+    int64_t chunk = (tokens * s->n_kv_heads + wgs - 1) / wgs;
     chunk = (chunk + quantum - 1) / quantum * quantum;
     if (chunk < 256) chunk = 256;
+    const int64_t cap = ((int64_t)s->max_ctx + quantum - 1) / quantum * quantum;
+    if (chunk > cap) chunk = cap;
     return (int)chunk;
 }
 
