@@ -279,3 +279,27 @@ def test_paper_gamma_10_at_32k():
     inp = wl.gen_attn_inputs(cfg)
     check(cfg, inp)
     check(cfg, inp, head_major=True, what="gamma10_32k head-major")
+
+
+def test_ctx_sum_hint_changes_the_plan_not_the_result():
+    """A ragged batch with and without the caller's sum-of-lengths hint: different KV splits, both within
+    tolerance of the oracle."""
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], batch=6, ctx=(200, 20000), paged=False, name="hint")
+    inp = wl.gen_attn_inputs(cfg)
+    s = inp.seqs
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    ctx, gam = torch.from_numpy(s.ctx_lens).cuda(), torch.from_numpy(s.gammas).cuda()
+    r = gu.rapid()
+    hint = int(s.ctx_lens.astype(np.int64).sum())
+    plain = r.attn_shape(q, k, s.max_ctx)
+    hinted = r.attn_shape(q, k, s.max_ctx, ctx_sum_hint=hint)
+    assert r.verify_attn_chunk(hinted) < r.verify_attn_chunk(plain)
+    import oracle
+    bs, ts, hs, ps = wl.kv_strides(cfg, s)
+    ref = oracle.verify_attn(inp.q, inp.k, inp.v, s.ctx_lens, oracle.KVLayout(bs, ts, hs), Hkv=cfg.n_kv_heads,
+                             scale=cfg.softmax_scale, gammas=s.gammas)
+    for h in (0, hint):
+        out = r.rapid_verify_attn(q, k, v, ctx, gammas=gam, max_ctx=s.max_ctx, softmax_scale=cfg.softmax_scale,
+                                  ctx_sum_hint=h)
+        torch.cuda.synchronize()
+        gu.assert_attn_close(gu.bf16_to_host(out), ref, f"hint={h}")
