@@ -13,6 +13,11 @@
  *                      (Eq. new_target / Eq. delta), the tail rule (Sec. 2.4),
  *                      the accept test and the residual / bonus draw (Alg. 1).
  *
+ * Around them: rapid_lm_head (the logits of the verification rows with the
+ * statistics rapid_accept_prestats consumes), rapid_kv_append / rapid_kv_commit
+ * (cache bookkeeping of a validation round), rapid_retrieve (the RAG drafter's
+ * chunk selection, Sec. 2.2) and rapid_hbm_read_probe (a measurement aid).
+ *
  * Conventions
  *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller
  *     owns all buffers; the library allocates no device memory, keeps no
@@ -23,6 +28,8 @@
  *   - Every function returns 0 or a negative rapid_status; nothing aborts or
  *     prints.  After RAPID_EHIP, rapid_last_hip_error() gives the HIP code.
  *   - Two calls that share a workspace must not overlap in time.
+ *   - rapid_create raises the dynamic-LDS limit of the kernels that need it; no other
+ *     call changes device or function state, so all of them may be stream-captured.
  */
 #ifndef RAPID_H
 #define RAPID_H
