@@ -113,8 +113,9 @@ size_t rapid_verify_attn_workspace_bytes(const rapid_ctx* ctx, const rapid_attn_
  *   q          bf16 [B, Qmax, Hq, d], contiguous
  *   k_cache    bf16, see rapid_attn_shape
  *   v_cache    bf16, same addressing as k_cache
- *   ctx_lens   int32 [B], gamma_b+1 <= ctx_lens[b] <= max_ctx (unchecked: device data)
- *   gammas     int32 [B] or NULL (-> shape->gamma for all), 0 <= gamma_b < Qmax
+ *   ctx_lens   int32 [B], gamma_b+1 <= ctx_lens[b] <= max_ctx; device data, so not checked: larger
+ *              values are clamped to max_ctx, a sequence of length 0 yields zeros
+ *   gammas     int32 [B] or NULL (-> shape->gamma for all), 0 <= gamma_b < Qmax (clamped to that range)
  *   page_table int32 [B, max_pages] when page_size > 0, else NULL
  *   out        bf16 [B, Qmax, Hq, d]
  *   lse_out    fp32 [B, Hq, Qmax] natural-log sum-exp of the scaled scores, or NULL

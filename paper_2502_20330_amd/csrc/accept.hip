@@ -95,6 +95,12 @@ __device__ __forceinline__ floatx4 load4(const float* row, int i, int V, bool ve
     return r;
 }
 
+// Drafts of sequence b; device data, so clamped to the range the buffers were sized for.
+__device__ __forceinline__ int seq_gamma(const AcceptLaunch& a, int b)
+{
+    return a.gammas ? min(max(a.gammas[b], 0), a.gmax) : a.gmax;
+}
+
 struct Ws {
     float2* st_t;     // [B][gmax+1][nch]  (raw max, sum exp((z-max)/T))
     float2* st_d;     // [B][gmax][nch]
@@ -128,7 +134,7 @@ __global__ void __launch_bounds__(kThreads) accept_row_stats(AcceptLaunch a, Ws 
 {
     __shared__ float sh[8];
     const int ch = blockIdx.x, y = blockIdx.y, b = blockIdx.z;
-    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int g = seq_gamma(a, b);
     const bool is_t = y <= a.gmax;
     const int k = is_t ? y : y - (a.gmax + 1);
     if (is_t ? (k > g) : (k >= g)) return;
@@ -213,7 +219,7 @@ __global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a,
 {
     __shared__ float sh[8];
     const int ch = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
-    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int g = seq_gamma(a, b);
     if (k >= g) return;
     const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
     const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
@@ -272,7 +278,7 @@ __device__ __forceinline__ void wave_combine(const float2* st, int nch, double i
 __global__ void __launch_bounds__(64) accept_decide(AcceptLaunch a, Ws ws)
 {
     const int k = blockIdx.x, b = blockIdx.y;
-    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int g = seq_gamma(a, b);
     if (k > g) return;
     // the drafted token's two logits are fetched while the statistics combine
     int x = -1;
@@ -363,7 +369,7 @@ __device__ __forceinline__ void weights(const RowCtx& c, int v, double& w, doubl
 __global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a, Ws ws)
 {
     const int ch = blockIdx.x, b = blockIdx.y;
-    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int g = seq_gamma(a, b);
     const int n = first_reject(ws, b, a.gmax, g);
     if (ch == 0) {
         // accepted drafts, then -1 (the draw fills slot n later)
@@ -431,7 +437,7 @@ __global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
     __shared__ int pick_chunk, last_chunk, pick_lo, pick_hi;
     __shared__ double chunk_base;
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int g = a.gammas ? a.gammas[b] : a.gmax;
+    const int g = seq_gamma(a, b);
     const int n = first_reject(ws, b, a.gmax, g);
     RowCtx c = make_row_ctx(a, ws, b, n, g);
     const int nsub = ws.nch * kSubs;             // partial sums of 256 entries, in vocabulary order

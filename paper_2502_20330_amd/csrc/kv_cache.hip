@@ -18,9 +18,10 @@ namespace {
 __global__ void __launch_bounds__(256) kv_append_rows(KvAppendLaunch a)
 {
     const int i = blockIdx.x, b = blockIdx.y;
-    const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
+    // device data: clamped to the rows k_new / v_new hold
+    const int Q = min(max(a.gammas ? a.gammas[b] : a.gamma, 0), a.Qmax - 1) + 1;
     if (i >= Q) return;
-    const int64_t tok = (int64_t)a.ctx_lens[b] - Q + i;
+    const int64_t tok = (int64_t)min(a.ctx_lens[b], a.max_ctx) - Q + i;
     if (tok < 0) return;                                   // malformed length: nothing to write
     int64_t base;
     if (a.page_shift >= 0) {

@@ -191,6 +191,7 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
     a.G = a.Hq / a.Hkv;
     a.D = shape->head_dim;
     a.gamma = shape->gamma;
+    a.max_ctx = shape->max_ctx;
     a.chunk = plan_chunk(ctx, shape);
     a.nsplit = (shape->max_ctx + a.chunk - 1) / a.chunk;
     a.RB = (a.Qmax * a.G + 15) / 16;
@@ -357,6 +358,7 @@ int rapid_kv_append(rapid_ctx* ctx, const rapid_attn_shape* shape, const void* k
     a.Hkv = shape->n_kv_heads;
     a.D = shape->head_dim;
     a.gamma = shape->gamma;
+    a.max_ctx = shape->max_ctx;
     a.bstride = shape->kv_batch_stride;
     a.tstride = shape->kv_token_stride;
     a.hstride = shape->kv_head_stride;

@@ -23,6 +23,7 @@ struct AttnLaunch {
     float* part_o;      // [B, Hkv, nsplit, RB*16, D] fp32, relative to part_m
     float* part_ml;     // [B, Hkv, nsplit, RB*16, 2] (running max in log2 units, sum)
     int32_t B, Qmax, Hq, Hkv, G, D, gamma;
+    int32_t max_ctx;    // host bound of ctx_lens
     int32_t chunk, nsplit, RB;
     int32_t rot;        // 1: dispatch slot x serves head (x + split) mod Hkv, 0: head x
     int32_t skew;       // tokens moved from the splits on odd dispatch slots to those on even ones
@@ -85,6 +86,7 @@ struct KvAppendLaunch {
     uint16_t* k_cache;
     uint16_t* v_cache;
     int32_t B, Qmax, Hkv, D, gamma;
+    int32_t max_ctx;
     int64_t bstride, tstride, hstride, pstride;   // elements
     int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
 };

@@ -284,6 +284,12 @@ __device__ __forceinline__ void pv_tile(WaveState<D, RB>& st, const bf16x8 (&pb)
     }
 }
 
+// Query positions of sequence b (gamma_b + 1); device data, so clamped to the rows q / out hold.
+__device__ __forceinline__ int seq_queries(const AttnLaunch& a, int b)
+{
+    return min(max(a.gammas ? a.gammas[b] : a.gamma, 0), a.Qmax - 1) + 1;
+}
+
 // Token range of split s of kv head h.  Splits come in pairs that cover 2*chunk
 // tokens; the member of a pair that runs on an even dispatch slot takes chunk + skew
 // tokens, the other chunk - skew (see the slot -> head mapping in the kernel).  An
@@ -315,11 +321,11 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     // suits caches whose heads interleave inside a token row.
     const int split = blockIdx.y, b = blockIdx.z;
     const int hkv = a.rot ? (int)((blockIdx.x + split) % a.Hkv) : (int)blockIdx.x;
-    const int L = a.ctx_lens[b];
+    const int L = min(a.ctx_lens[b], a.max_ctx);        // device data: never address past the planned range
     const int c0 = split_begin(a, split, hkv);
     if (c0 >= L) return;                             // this split holds no token of sequence b
     const int c1 = min(split_end(a, split, hkv), L);
-    const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
+    const int Q = seq_queries(a, b);
     const int R = Q * a.G;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -518,7 +524,7 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
     __shared__ float red[2][4];
     const int row = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
     const int d = threadIdx.x;
-    const int Q = (a.gammas ? a.gammas[b] : a.gamma) + 1;
+    const int Q = seq_queries(a, b);
     const int R = Q * a.G, RP = a.RB * 16;
     const int qi = row / a.G, qg = row % a.G;
     const int h = hkv * a.G + qg;
@@ -548,7 +554,7 @@ __global__ void __launch_bounds__(D) verify_attn_merge(AttnLaunch a)
             ls = ml[1];
         }
         if (s0 == 0) {
-            const int L = a.ctx_lens[b];
+            const int L = min(a.ctx_lens[b], a.max_ctx);
             ns = min(L / a.chunk + 2, a.nsplit);      // splits that hold a token of this sequence
             while (ns > 0 && split_begin(a, ns - 1, hkv) >= L) --ns;
         }

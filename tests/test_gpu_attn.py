@@ -303,3 +303,28 @@ def test_ctx_sum_hint_changes_the_plan_not_the_result():
                                   ctx_sum_hint=h)
         torch.cuda.synchronize()
         gu.assert_attn_close(gu.bf16_to_host(out), ref, f"hint={h}")
+
+
+def test_out_of_range_device_values_are_clamped():
+    """ctx_lens and gammas are device data the host cannot validate: values outside their ranges are clamped
+    (gamma_b to [0, Qmax-1], ctx_lens[b] to max_ctx) instead of steering any access out of bounds, and a
+    sequence of length 0 yields zeros.  The valid sequences of the same batch are unaffected."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=4, ctx=(900, 900), gamma_choices=(3,), name="clamp")
+    inp = wl.gen_attn_inputs(cfg)
+    s = inp.seqs
+    q, k, v = (gu.bf16_to_dev(x) for x in (inp.q, inp.k, inp.v))
+    bad_ctx = np.array([900, 900, 900 + 5000, 0], dtype=np.int32)
+    bad_gam = np.array([3, 99, -7, 3], dtype=np.int32)
+    out = gu.rapid().rapid_verify_attn(q, k, v, torch.from_numpy(bad_ctx).cuda(), gammas=torch.from_numpy(bad_gam).cuda(),
+                                       max_ctx=900, softmax_scale=cfg.softmax_scale)
+    torch.cuda.synchronize()
+    got = gu.bf16_to_host(out)
+    assert np.all(np.isfinite(got))
+    import oracle
+    bs, ts, hs, ps = wl.kv_strides(cfg, s)
+    eff_ctx = np.array([900, 900, 900, 900], dtype=np.int32)
+    eff_gam = np.array([3, cfg.q_max - 1, 0, 3], dtype=np.int32)
+    ref = oracle.verify_attn(inp.q, inp.k, inp.v, eff_ctx, oracle.KVLayout(bs, ts, hs), Hkv=cfg.n_kv_heads,
+                             scale=cfg.softmax_scale, gammas=eff_gam)
+    gu.assert_attn_close(got[:3], ref[:3], "clamped sequences")
+    assert np.all(got[3] == 0.0)
