@@ -196,7 +196,7 @@ int main()
         return 2;
     }
     for (int b = 0; b < B; ++b) {
-        bool near = dm[b] <= 1e-5;
+        bool near = dm[b] <= 1e-10;
         for (int kk = 0; kk < gammas_h[b]; ++kk) near = near || am[(size_t)b * gmax + kk] <= 1e-5;
         const bool same = n_acc[b] == rn[b] &&
                           memcmp(&toks[(size_t)b * (gmax + 1)], &rt[(size_t)b * (gmax + 1)], (gmax + 1) * 4) == 0;

@@ -1,7 +1,9 @@
 """GPU parity: rapid_accept (C ABI, gfx950 kernels) against the float64 oracle.
 Accepted-prefix length and emitted tokens must match bit for bit, except
 sequences whose decisive accept test lies within 1e-5 of its uniform, or whose
-draw lands within 1e-5 (normalised) of a CDF edge; those are counted and printed."""
+draw lands within 1e-10 (normalised) of a CDF edge.  All inputs are seeded, so the
+number of such sequences is a constant of each test and is asserted exactly (0
+unless a test says otherwise)."""
 import numpy as np
 import pytest
 import torch
@@ -21,7 +23,7 @@ def _gpu():
     yield
 
 
-def check(cfg, acc, what, *, eta=None, temperature=None, tail_alpha=None, use_gammas=True, max_exempt_frac=0.2):
+def check(cfg, acc, what, *, eta=None, temperature=None, tail_alpha=None, use_gammas=True, exempt=0):
     eta = cfg.eta if eta is None else eta
     temperature = cfg.temperature if temperature is None else temperature
     tail_alpha = cfg.tail_alpha if tail_alpha is None else tail_alpha
@@ -29,7 +31,7 @@ def check(cfg, acc, what, *, eta=None, temperature=None, tail_alpha=None, use_ga
     st = gu.compare_accept(gpu, ref, acc.gammas if use_gammas else None, cfg.gamma_max)
     print(f"[{what}] {st} mean_accepted={ref.n_accepted.mean():.2f}")
     assert st["n_mismatch"] == 0 and st["token_mismatch"] == 0, st
-    assert st["exempt_sequences"] <= max(1, int(max_exempt_frac * st["sequences"])), st
+    assert st["exempt_sequences"] == exempt, st
     assert st["max_ratio_rel_err"] < 1e-4, st
     # shape of the token rows: accepted drafts, one drawn token in [0, V), then -1
     n, tok, _ = gpu
@@ -55,7 +57,7 @@ def test_tiny_many_sequences_all_branches():
 @pytest.mark.parametrize("V", [1, 2, 3, 5, 1023, 1024, 1025, 4099, 50257])
 def test_vocab_sizes_and_unaligned_rows(V):
     cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=V, draft_noise_std=1.0, gamma_choices=(3,))
-    check(cfg, wl.gen_accept_inputs(cfg, batch=16), f"V={V}", max_exempt_frac=0.5)
+    check(cfg, wl.gen_accept_inputs(cfg, batch=16), f"V={V}")
 
 
 @pytest.mark.parametrize("eta,T,alpha", [(0.0, 1.0, 0.1), (1.0, 1.0, 0.0), (5.0, 1.0, 0.1), (20.0, 1.0, 0.1),
@@ -137,7 +139,7 @@ def test_llama_vocab_full_size():
     cfg = wl.CONFIGS["llama8b_32k"]
     acc = wl.gen_accept_inputs(cfg)
     for eta in (1.0, 0.25, 0.5):
-        check(cfg, acc, f"V=128256 B=1 eta={eta}", eta=eta, max_exempt_frac=1.0)
+        check(cfg, acc, f"V=128256 B=1 eta={eta}", eta=eta)
 
 
 def test_llama_vocab_many_sequences():

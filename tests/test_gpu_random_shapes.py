@@ -76,6 +76,7 @@ def test_random_accept_case(c):
     gpu, ref = gu.run_accept_case(acc, eta=c["eta"], temperature=c["T"], tail_alpha=c["alpha"])
     st = gu.compare_accept(gpu, ref, acc.gammas, cfg.gamma_max)
     assert st["n_mismatch"] == 0 and st["token_mismatch"] == 0, (c, st)
+    assert st["exempt_sequences"] == 0, (c, st)            # seeded inputs: no near-tie is ever used
     assert st["max_ratio_rel_err"] < 1e-4, (c, st)
 
 

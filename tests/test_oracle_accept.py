@@ -407,3 +407,67 @@ def test_worked_example_fixture():
                           np.array([[case["r"], case["u"]]], np.float32), eta=gold["eta"])
         assert int(r.n_accepted[0]) == case["n_accepted"]
         assert int(r.out_tokens[0, 0]) == case["token"]
+
+
+# ---------------------------------------------------------------- the margins the GPU comparison relies on
+def test_accept_margin_hand_cases():
+    """accept_margin = |min(1, rho) - r| (Alg. 1 accept test).  eta = 0, V = 2: p = (1/4, 3/4), q = (1/2, 1/2),
+    so rho(token 0) = 1/2 and rho(token 1) = 3/2 (clamped to 1).  The uniform is placed a known distance
+    from the threshold on either side; the margin must be that distance, and the decision must follow the
+    side."""
+    z = np.log(np.array([[1.0, 3.0], [1.0, 3.0]], dtype=np.float64)).astype(np.float32)[None]    # [1, 2, 2]
+    zq = np.zeros((1, 1, 2), dtype=np.float32)
+    p0 = float(sp_softmax(z[0, 0].astype(np.float64))[0])            # 0.25 up to the rounding of ln 3 to fp32
+    for tok, thr in ((0, 2.0 * p0), (1, 1.0)):
+        for delta in (+5e-6, -5e-6, +0.2, -0.3):
+            u = np.float32(thr + delta)
+            if not (0.0 <= u < 1.0):
+                continue
+            r = oracle.accept(z, zq, np.array([[tok]], np.int32), np.array([[u, 0.5]], np.float32), eta=0.0,
+                              tail_alpha=0.0)
+            want = abs(thr - float(u))
+            assert abs(r.accept_margin[0, 0] - want) < 1e-12, (tok, delta, r.accept_margin, want)
+            assert int(r.n_accepted[0]) == (1 if float(u) <= thr else 0)
+            assert abs(r.ratio[0, 0] - (2.0 * p0 if tok == 0 else 2.0 * (1.0 - p0))) < 1e-12
+
+
+def test_draw_margin_hand_cases():
+    """draw_margin = distance of u to the nearer edge of the drawn token's interval of the NORMALISED
+    cumulative distribution.  Residual at eta = 0 with p = (1/8, 2/8, 5/8), q = (.8, .1, .1): weights
+    (0, .15, .525), W = .675, interval edges 0 | 0 | 2/9 | 1.  Bonus draw from p: edges 0 | 1/8 | 3/8 | 1."""
+    z = np.log(np.array([1.0, 2.0, 5.0]))
+    zq = np.log(np.array([0.8, 0.1, 0.1]))
+    zt = np.stack([z, z]).astype(np.float32)[None]
+    zd = zq.astype(np.float32)[None, None]
+    p = sp_softmax(zt[0, 0].astype(np.float64))
+    q = sp_softmax(zd[0, 0].astype(np.float64))
+    w = np.maximum(p - q, 0.0)
+    edges = np.concatenate([[0.0], np.cumsum(w) / w.sum()])
+    assert abs(edges[2] - 2.0 / 9.0) < 1e-6
+    # token 0 is drafted and rejected with r = 0.9 (rho = p0/q0 = 0.156)
+    for u, tok in ((0.2, 1), (0.1, 1), (0.23, 2), (0.9, 2), (0.0, 1)):
+        uf = np.float32(u)
+        r = oracle.accept(zt, zd, np.array([[0]], np.int32), np.array([[0.9, uf]], np.float32), eta=0.0,
+                          tail_alpha=0.0)
+        assert r.n_accepted[0] == 0 and r.out_tokens[0, 0] == tok, (u, r.out_tokens)
+        want = min(float(uf) - edges[tok], edges[tok + 1] - float(uf))
+        assert abs(r.draw_margin[0] - want) < 1e-12, (u, r.draw_margin, want)
+    # bonus row (draft accepted with r = 0): draw from p
+    pe = np.concatenate([[0.0], np.cumsum(p)])
+    for u, tok in ((0.05, 0), (0.124, 0), (0.126, 1), (0.37, 1), (0.38, 2), (0.99, 2)):
+        uf = np.float32(u)
+        r = oracle.accept(zt, zd, np.array([[2]], np.int32), np.array([[0.0, uf]], np.float32), eta=0.0,
+                          tail_alpha=0.0)
+        assert r.n_accepted[0] == 1 and r.out_tokens[0, 1] == tok, (u, r.out_tokens)
+        want = min(float(uf) - pe[tok], pe[tok + 1] - float(uf))
+        assert abs(r.draw_margin[0] - want) < 1e-12, (u, r.draw_margin, want)
+
+
+def test_draw_margin_is_zero_when_the_target_rounds_up_to_the_total():
+    """A uniform of exactly 1 (outside the [0, 1) contract) makes u * W equal W, no running sum exceeds
+    it, and the draw falls back to the last entry with weight; the margin of that case is 0."""
+    zt = np.log(np.array([[1.0, 2.0, 5.0, 1e-30], [1.0, 2.0, 5.0, 1e-30]])).astype(np.float32)[None]
+    zd = np.zeros((1, 1, 4), dtype=np.float32)
+    r = oracle.accept(zt, zd, np.array([[0]], np.int32), np.array([[0.0, 1.0]], np.float32), eta=0.0, tail_alpha=0.0)
+    assert r.n_accepted[0] == 1 and r.draw_margin[0] == 0.0
+    assert r.out_tokens[0, 1] == 3                       # the last entry whose weight is positive

@@ -35,6 +35,24 @@ def test_hand_case_threshold_and_top_k():
     assert sel.tolist() == []
 
 
+def test_margin_is_the_smallest_distance_to_a_decision_boundary():
+    """Same hand case (cosines 1, 0, 0.7071, -1, 0.6, 1).  The margin is the smaller of (a) the gap between
+    the k-th and the (k+1)-th similarity in rank order and (b) the smallest |similarity - threshold|."""
+    q = np.array([1.0, 0.0], dtype=np.float32)
+    emb = np.array([[1, 0], [0, 1], [1, 1], [-1, 0], [3, 4], [2, 0]], dtype=np.float32)
+    r2 = 2 ** -0.5
+    # k = 3: ranks 1, 1, .7071 | .6 -> gap .1071; nearest similarity to the threshold 0.3 is 0 or 0.6 (0.3 away)
+    assert abs(oracle.retrieve(emb, q, 3, 0.3)[2] - (r2 - 0.6)) < 1e-12
+    # k = 2: the k-th and (k+1)-th values are 1 (chunk 5) and .7071 -> gap .2929 < .3
+    assert abs(oracle.retrieve(emb, q, 2, 0.3)[2] - (1.0 - r2)) < 1e-12
+    # k = 1: the two best are equal -> gap 0
+    assert oracle.retrieve(emb, q, 1, 0.3)[2] == 0.0
+    # threshold close to a similarity decides: |0.6 - 0.58| = 0.02 < every rank gap
+    assert abs(oracle.retrieve(emb, q, 3, 0.58)[2] - (0.6 - 0.58)) < 1e-9
+    # k = n: no rank boundary, only the threshold counts: nearest is 0.7071 - 0.65
+    assert abs(oracle.retrieve(emb, q, 6, 0.65)[2] - (0.65 - 0.6)) < 1e-9
+
+
 def test_scaling_a_chunk_does_not_change_its_similarity_and_zero_vectors_score_zero():
     emb, q = wl.gen_retrieval_inputs(50, dim=64)
     a, _, _ = oracle.retrieve(emb, q, 5, 0.3)
