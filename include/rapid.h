@@ -47,7 +47,8 @@ typedef enum rapid_status {
     RAPID_EALIGN = -2,        /* q/k/v/out not 16-byte aligned, or a stride not a multiple of 8 elements  */
     RAPID_EUNSUPPORTED = -3,  /* head_dim not 64/128, (gamma+1)*group > 80, page size not a power of two >= 16 */
     RAPID_EWORKSPACE = -4,    /* workspace NULL, misaligned or smaller than the *_workspace_bytes() answer */
-    RAPID_EHIP = -5           /* a HIP runtime call failed */
+    RAPID_EHIP = -5,          /* a HIP runtime call failed */
+    RAPID_ETOOLARGE = -6      /* rapid_verify_attn_static: the shape needs more than RAPID_STATIC_SCRATCH_BYTES */
 } rapid_status;
 
 typedef struct rapid_ctx rapid_ctx;   /* opaque; caches device properties, owns no device memory */
@@ -127,6 +128,29 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
                       const int32_t* page_table,
                       void* out, float* lse_out,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * rapid_verify_attn for callers that cannot allocate device memory at all: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels,
+ * same argument rules and results as rapid_verify_attn, but the split partials go to a static
+ * device array inside the library (RAPID_STATIC_SCRATCH_BYTES per GPU, held from the moment the
+ * library is loaded until the process ends) instead of a caller-supplied workspace; the call
+ * allocates and frees nothing.
+ *   - A shape whose rapid_verify_attn_workspace_bytes() exceeds RAPID_STATIC_SCRATCH_BYTES is
+ *     refused with RAPID_ETOOLARGE (all other errors as for rapid_verify_attn).  The limit covers
+ *     every configuration this library is benchmarked on (the largest, eight ragged 128K-token
+ *     sequences, needs 21 MB).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU
+ *     (different streams, or different contexts on that GPU) race.  Calls on one stream are safe.
+ *   - The array keeps whatever the previous call left; nothing in it has to start at zero (slots of
+ *     splits that hold no token are never read), so the call clears nothing.
+ */
+#define RAPID_STATIC_SCRATCH_BYTES (32u << 20)
+int rapid_verify_attn_static(rapid_ctx* ctx, const rapid_attn_shape* shape,
+                             const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* ctx_lens, const int32_t* gammas,
+                             const int32_t* page_table,
+                             void* out, float* lse_out, void* stream);
 
 /* Bytes of device workspace rapid_accept needs (0 on bad sizes). */
 size_t rapid_accept_workspace_bytes(const rapid_ctx* ctx, int batch, int gamma_max, int vocab);

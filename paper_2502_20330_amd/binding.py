@@ -16,9 +16,11 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "librapid.so")
 
 RAPID_OK = 0
-RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP = -1, -2, -3, -4, -5
+RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP, RAPID_ETOOLARGE = -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 32 << 20
 EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
+           "rapid_verify_attn_static",
            "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
            "rapid_lm_head_chunk", "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_kv_append", "rapid_kv_commit",
            "rapid_retrieve", "rapid_hbm_read_probe"]
@@ -70,6 +72,9 @@ def load_library() -> ctypes.CDLL:
     lib.rapid_verify_attn.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape), vp, vp, vp, i32p, i32p, i32p,
                                       vp, f32p, vp, ctypes.c_size_t, vp]
     lib.rapid_verify_attn.restype = ctypes.c_int
+    lib.rapid_verify_attn_static.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape), vp, vp, vp, i32p, i32p, i32p,
+                                             vp, f32p, vp]
+    lib.rapid_verify_attn_static.restype = ctypes.c_int
     lib.rapid_accept_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.rapid_accept_workspace_bytes.restype = ctypes.c_size_t
     lib.rapid_accept.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, f32p, f32p, i32p, i32p,
@@ -203,6 +208,22 @@ class Rapid:
         rc = self.lib.rapid_verify_attn(self._ctx, ctypes.byref(shape), _dptr(q), _dptr(k_cache), _dptr(v_cache),
                                         _dptr(ctx_lens), _dptr(gammas), _dptr(page_table), _dptr(out),
                                         _dptr(lse_out), _dptr(ws), ws.numel(), _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return out
+
+    def rapid_verify_attn_static(self, q, k_cache, v_cache, ctx_lens, gamma: Optional[int] = None, *, gammas=None,
+                                 page_table=None, max_ctx: Optional[int] = None,
+                                 softmax_scale: Optional[float] = None, chunk_tokens: int = 0, out, lse_out=None,
+                                 ctx_sum_hint: int = 0):
+        """The allocation-free form of :meth:`rapid_verify_attn`: the caller passes `out`, the split partials go
+        to the library's static device array, and neither this method nor the library allocates anything."""
+        if max_ctx is None:
+            max_ctx = k_cache.shape[1] if page_table is None else page_table.shape[1] * k_cache.shape[1]
+        shape = self.attn_shape(q, k_cache, max_ctx, gamma=gamma, page_table=page_table, softmax_scale=softmax_scale,
+                                chunk_tokens=chunk_tokens, ctx_sum_hint=ctx_sum_hint)
+        rc = self.lib.rapid_verify_attn_static(self._ctx, ctypes.byref(shape), _dptr(q), _dptr(k_cache),
+                                               _dptr(v_cache), _dptr(ctx_lens), _dptr(gammas), _dptr(page_table),
+                                               _dptr(out), _dptr(lse_out), _stream_ptr(self.device))
         _check(self.lib, rc, self._ctx)
         return out
 

@@ -3,6 +3,12 @@
 
 #include "rapid_internal.h"
 
+// Scratch memory of the allocation-free entry point (rapid_verify_attn_static): one copy per
+// GPU that loads this library, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address is looked up once per context
+// (rapid_create, with the context's device current) and kept in rapid_ctx::static_scratch.
+static __device__ __align__(256) unsigned char scratch[RAPID_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -115,11 +121,14 @@ int rapid_create(rapid_ctx** out, int device)
     hipError_t ec = configure_verify_attn();
     if (ec == hipSuccess) ec = configure_lm_head();
     if (ec == hipSuccess) ec = configure_hbm_read_probe();
+    void* scratch_ptr = nullptr;                      // this device's copy of `scratch`
+    if (ec == hipSuccess) ec = hipGetSymbolAddress(&scratch_ptr, HIP_SYMBOL(scratch));
     (void)hipSetDevice(prev);
-    if (ec != hipSuccess) return RAPID_EHIP;
+    if (ec != hipSuccess || !scratch_ptr) return RAPID_EHIP;
     rapid_ctx* c = new (std::nothrow) rapid_ctx;
     if (!c) return RAPID_EINVAL;
     c->device = device;
+    c->static_scratch = scratch_ptr;
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c->last_hip_error = 0;
     *out = c;
@@ -137,6 +146,7 @@ const char* rapid_strerror(int status)
         case RAPID_EUNSUPPORTED: return "shape not supported";
         case RAPID_EWORKSPACE: return "workspace missing, misaligned or too small";
         case RAPID_EHIP: return "HIP runtime error";
+        case RAPID_ETOOLARGE: return "shape needs more scratch memory than the allocation-free entry point holds";
     }
     return "unknown status";
 }
@@ -218,6 +228,20 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
     hipError_t e = launch_verify_attn(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
+}
+
+int rapid_verify_attn_static(rapid_ctx* ctx, const rapid_attn_shape* shape,
+                             const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* ctx_lens, const int32_t* gammas, const int32_t* page_table,
+                             void* out, float* lse_out, void* stream)
+{
+    if (!ctx) return RAPID_EINVAL;
+    const int rc = check_attn_shape(shape);
+    if (rc != RAPID_OK) return rc;
+    if (rapid_verify_attn_workspace_bytes(ctx, shape) > (size_t)RAPID_STATIC_SCRATCH_BYTES) return RAPID_ETOOLARGE;
+    // same kernels, same argument checks; the split partials go to this device's static array
+    return rapid_verify_attn(ctx, shape, q, k_cache, v_cache, ctx_lens, gammas, page_table, out, lse_out,
+                             ctx->static_scratch, (size_t)RAPID_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t rapid_accept_workspace_bytes(const rapid_ctx*, int batch, int gamma_max, int vocab)

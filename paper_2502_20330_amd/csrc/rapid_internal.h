@@ -8,6 +8,7 @@ struct rapid_ctx {
     int device;
     int n_cu;
     int last_hip_error;
+    void* static_scratch;   // device address of this GPU's copy of the library's static scratch array
 };
 
 // ---- verify attention (verify_attn.hip)
