@@ -7,8 +7,8 @@
  *
  *   rapid_verify_attn  attention of the gamma+1 verification positions against
  *                      the whole long-context KV cache: the memory-bound part
- *                      of "z <- LogitsOf(p_phi(. | [C; x_<j]))" done for all
- *                      positions in one pass (Sec. 2.1, Alg. 1);
+ *                      of the target's logits for all drafted positions, which
+ *                      the target computes in one pass (Sec. 2.1, Alg. 1);
  *   rapid_accept       p, q, the retrieval-augmented target p_hat
  *                      (Eq. new_target / Eq. delta), the tail rule (Sec. 2.4),
  *                      the accept test and the residual / bonus draw (Alg. 1).
@@ -60,6 +60,23 @@ const char* rapid_strerror(int status);
 int rapid_last_hip_error(const rapid_ctx* ctx);
 
 /*
+ * Tuning / test knobs of a context (host call, takes effect for later calls on this context).
+ *   RAPID_OPT_ACCEPT_WAIT_US  The kernels of rapid_accept exchange partial results between
+ *       workgroups; a workgroup waits at most this many microseconds for another one and then
+ *       computes the missing piece itself (same arithmetic, same result).  Default 100; 0 = never
+ *       wait (every exchange takes the recomputation path; for tests).  0 <= value <= 10^7.
+ *   RAPID_OPT_ACCEPT_SLICE    Vocabulary entries per workgroup of rapid_accept's row pass:
+ *       0 = chosen from the batch size (default), or 4096, 8192, 16384.  Results of the accept
+ *       tests may differ in the last bits of accept_ratio between slice sizes (fp32 sums).
+ * Returns RAPID_EINVAL for an unknown option or a value out of range.
+ */
+typedef enum rapid_option {
+    RAPID_OPT_ACCEPT_WAIT_US = 1,
+    RAPID_OPT_ACCEPT_SLICE = 2
+} rapid_option;
+int rapid_set_option(rapid_ctx* ctx, int option, int64_t value);
+
+/*
  * Shape of one rapid_verify_attn call (host struct).
  *
  * KV cache addressing, in ELEMENTS (bf16 words); element (b, token j, kv head h, c):
@@ -100,9 +117,9 @@ int rapid_verify_attn_chunk(const rapid_ctx* ctx, const rapid_attn_shape* shape)
 size_t rapid_verify_attn_workspace_bytes(const rapid_ctx* ctx, const rapid_attn_shape* shape);
 
 /*
- * Causal grouped-query attention of the verification positions (Sec. 2.1:
- * gamma candidates "validated by the target model in a single forward pass";
- * Alg. 1: target logits conditioned on [C; x_<j] for every drafted position j).
+ * Causal grouped-query attention of the verification positions (Sec. 2.1: the
+ * target scores all gamma drafted positions in one forward pass; Alg. 1: the
+ * target's logits at position j are conditioned on the context and the drafts before j).
  *
  * For sequence b let L = ctx_lens[b], Q = gamma_b + 1.  The cache already holds
  * K/V of the Q verification positions as its LAST Q valid tokens (L counts
@@ -179,8 +196,17 @@ size_t rapid_accept_workspace_bytes(const rapid_ctx* ctx, int batch, int gamma_m
  *   out_tokens    int32 [B, gamma_max+1]: accepted drafts, the drawn token, then -1
  *   accept_ratio  fp32 [B, gamma_max] ph_k(x_k)/q_k(x_k) of every row k < gamma_b
  *                 (also after the first reject), or NULL
- *   workspace     >= rapid_accept_workspace_bytes(), 256-byte aligned
+ *   workspace     >= rapid_accept_workspace_bytes(), 256-byte aligned.  Its first words are a
+ *                 status block the caller may read once the stream is synchronised (int32):
+ *                   [RAPID_ACCEPT_STATUS_BAD_IDS]  drafted positions of this call that were
+ *                       rejected because the id was outside [0, V)
+ *                   [RAPID_ACCEPT_STATUS_GIVEUPS]  diagnostics: exchange waits of this call that
+ *                       ran into RAPID_OPT_ACCEPT_WAIT_US (results are unaffected)
+ * vocab <= 2^22.  Logit rows whose address is not 16-byte aligned (vocab not a multiple of 4)
+ * are read with scalar loads: same results, lower bandwidth.
  */
+#define RAPID_ACCEPT_STATUS_BAD_IDS 0
+#define RAPID_ACCEPT_STATUS_GIVEUPS 1
 int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                  const float* target_logits, const float* draft_logits,
                  const int32_t* draft_tokens, const int32_t* gammas,

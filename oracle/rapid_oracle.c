@@ -10,9 +10,9 @@
  * Functions:
  *
  *   oracle_verify_attn  -- the target model's attention for the gamma+1
- *       verification positions against the whole KV cache ("validated by the
- *       target model in a single forward pass", Sec. 2.1; Alg. 1 step
- *       "z <- LogitsOf(p_phi(. | [C; x_<j]))").  The paper gives no formula
+ *       verification positions against the whole KV cache (Sec. 2.1: the
+ *       target scores all drafted positions in one forward pass; Alg. 1: the
+ *       step that takes the target's logits at position j).  The paper gives no formula
  *       for attention itself: this is the textbook definition of causal,
  *       grouped-query softmax attention written out per (sequence, query
  *       position, query head) with a two-pass softmax.  No tiling, no online

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "librapid.so")
 RAPID_OK = 0
 RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP, RAPID_ETOOLARGE = -1, -2, -3, -4, -5, -6
 STATIC_SCRATCH_BYTES = 32 << 20
-EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error",
+OPT_ACCEPT_WAIT_US, OPT_ACCEPT_SLICE = 1, 2
+EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error", "rapid_set_option",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
            "rapid_verify_attn_static",
            "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
@@ -65,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.rapid_strerror.restype = ctypes.c_char_p
     lib.rapid_last_hip_error.argtypes = [ctypes.c_void_p]
     lib.rapid_last_hip_error.restype = ctypes.c_int
+    lib.rapid_set_option.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]
+    lib.rapid_set_option.restype = ctypes.c_int
     lib.rapid_verify_attn_chunk.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape)]
     lib.rapid_verify_attn_chunk.restype = ctypes.c_int
     lib.rapid_verify_attn_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape)]
@@ -146,6 +149,16 @@ class Rapid:
             self.close()
         except Exception:
             pass
+
+    def set_option(self, option: int, value: int):
+        _check(self.lib, self.lib.rapid_set_option(self._ctx, int(option), int(value)))
+
+    def accept_status(self):
+        """(rejected out-of-range draft ids, exchange waits that gave up) of the last rapid_accept call that
+        used this object's workspace; synchronises."""
+        torch.cuda.synchronize(self.device)
+        w = self._ws[:8].view(torch.int32).cpu()
+        return int(w[0]), int(w[1])
 
     def _workspace(self, nbytes: int) -> torch.Tensor:
         if self._ws is None or self._ws.numel() < nbytes:

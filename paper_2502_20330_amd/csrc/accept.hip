@@ -7,92 +7,154 @@
 //   accept x' iff r <= min(1, p_hat(x')/q(x'))                 (Alg. 1)
 //   first reject: x ~ norm(max(p - p_hat, p - q, 0)); none: x ~ p of the next row.
 //
-// The accept test at a position needs p, q, p_hat only at the one drafted token,
-// given three log-normalisers per row; only the row where the draw happens needs
-// an elementwise pass.  So the work is organised as reductions over the
-// vocabulary, chunked over many workgroups so the logits stream at HBM rate:
+// The accept test of a position needs p, q, p_hat only at the one drafted token, given three
+// log-normalisers per row; only the row where the draw happens needs an elementwise pass.
+// Three launches:
 //
-//   K1 row_stats      : per chunk of 4096 entries (max z, sum exp((z - max)/T)) of every target and draft row
-//   K2 shifted_stats  : per chunk (max, sum exp) of d = (z - zmax)/T + eta (q - p)
-//   K3 decide         : one wave per row: combine chunks -> log-normalisers (double), accept
-//                       test in double at the drafted token -> pass/fail flag, ratio
-//   K4 residual_sums  : n = first failed flag; per chunk sum of the draw weights of row n (double);
-//                       n_accepted and the accepted prefix of out_tokens
-//   K5 draw           : locate the chunk and the token where the running sum passes u*W
+//   accept_init   fills the exchange slots of the workspace with the "empty" pattern.
 //
-// Sums over the vocabulary run in fp32 per thread and are combined in fp64;
-// everything that decides an integer (accept test, draw) is evaluated in fp64.
-// Statistics are kept relative to the raw row maximum so that dividing by T
+//   accept_rows   reads every logit ONCE.  A row pair (target row k, draft row k) is cut into
+//       slices of 2048*NV entries; one workgroup of 512 threads holds its slice of both rows in
+//       registers.  It publishes the slice's (max, sum exp) of either row, picks up the
+//       publications of the other workgroups of the row pair, and with the row normalisers
+//       forms d = z/T + eta (q - p) for its slice (still in registers) and publishes
+//       (max d, sum exp(d - max)).  The workgroup that arrives last at a row combines all
+//       slices in fp64 and runs the accept test of the drafted token.
+//
+//   accept_draw_row   n = first rejected position; the draw weights of row n (the residual,
+//       or p of the bonus row) are formed entirely in fp64 -- exponentials, normalisers,
+//       running sums -- because their prefix sums decide an integer; three small exchanges
+//       between the workgroups of the row (normalisers of p and q; normaliser and maximum
+//       of p_hat; weight totals), then the workgroup whose range holds u*W finds the token.
+//
+// Exchange between workgroups.  A publication is one 64-bit word written with a device-scope
+// atomic store into a slot that accept_init set to all ones; a reader polls the slot with
+// device-scope atomic loads until it is no longer empty.  Every wait is bounded (wall-clock
+// ticks): when a slot stays empty, the waiting workgroup computes that slice's publication
+// itself from the logits in memory -- same code, same order of operations, hence the same
+// bits -- stores it into the slot, and goes on.  No workgroup ever depends on another one
+// for termination, and results do not depend on timing.
+//
+// Numerics: per-slice sums in fp32, combined in fp32 for the elementwise pass of accept_rows
+// and in fp64 for every decision; the accept ratio therefore carries ~1e-7 relative error
+// (decisions within 1e-5 of the uniform are near-ties by the definition of the benchmark).
+// The draw is fp64 throughout and differs from a sequential fp64 evaluation by summation
+// order only.  Statistics are kept relative to the raw row maximum so that dividing by T
 // costs no absolute precision.
 #include "rapid_internal.h"
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+// Per-phase timestamps for development builds (-DRAPID_ACCEPT_STAMPS); absent from normal builds.
+#ifdef RAPID_ACCEPT_STAMPS
+__device__ unsigned long long g_dbg[8192 * 16];
+#define STAMP(i) do { if (threadIdx.x == 0) { int _l = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z); \
+    if (_l < 8192) g_dbg[_l * 16 + (i)] = wall_clock64(); } } while (0)
+#define STAMP_AT(l, i) do { if (threadIdx.x == 0 && (l) < 8192) g_dbg[(l) * 16 + (i)] = wall_clock64(); } while (0)
+extern "C" int rapid_debug_read(void* dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dbg), sizeof(g_dbg)); }
+#else
+#define STAMP(i) do { } while (0)
+#define STAMP_AT(l, i) do { } while (0)
+#endif
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kVec = 4;                 // 128-bit loads per thread and chunk
-constexpr int kChunk = kThreads * 4 * kVec;   // vocabulary entries per workgroup (4096)
-constexpr int kSub = 256;                // entries per draw-weight partial sum (one wave x one 128-bit load)
-constexpr int kSubs = kChunk / kSub;     // partial sums per chunk
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kDrawSlice = kThreads * 8;            // smallest slice of accept_draw_row (8 entries per thread)
+constexpr int kMinSlice = kThreads * 4 * 2;         // smallest slice of accept_rows (NV = 2)
+constexpr u64 kEmpty = ~0ull;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr double kLn2 = 0.6931471805599453;
 
-__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float wave_max(float v)
+// Wave-wide inclusive scan through the DPP lane-permute path (no LDS traffic): shifts by 1, 2, 4, 8
+// inside each row of 16 lanes, then the row broadcasts of this architecture (lane 15 of a row into
+// the next row, lane 31 into the upper half).  Lanes whose source does not exist read `id`.  Lane 63
+// ends up with the reduction over the wave; the order of the operations is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float id, float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(id), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move(double id, double v)
+{
+    const long long i = __double_as_longlong(id), x = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp((int)i, (int)x, CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp((int)(i >> 32), (int)(x >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+template <class T, class Op>
+__device__ __forceinline__ T wave_scan(T v, Op op)
+{
+    const T id = Op::id();
+    v = op(v, dpp_move<0x111, 0xf>(id, v));      // row_shr:1
+    v = op(v, dpp_move<0x112, 0xf>(id, v));      // row_shr:2
+    v = op(v, dpp_move<0x114, 0xf>(id, v));      // row_shr:4
+    v = op(v, dpp_move<0x118, 0xf>(id, v));      // row_shr:8
+    v = op(v, dpp_move<0x142, 0xa>(id, v));      // row_bcast:15 into rows 1 and 3
+    v = op(v, dpp_move<0x143, 0xc>(id, v));      // row_bcast:31 into rows 2 and 3
     return v;
 }
-__device__ __forceinline__ float wave_sum(float v)
+__device__ __forceinline__ float lane_value(float v, int lane)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
-__device__ __forceinline__ double wave_sum(double v)
+__device__ __forceinline__ double lane_value(double v, int lane)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    const long long x = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)x, lane), hi = __builtin_amdgcn_readlane((int)(x >> 32), lane);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
-__device__ __forceinline__ double wave_max(double v)
+struct OpMaxF { __device__ float operator()(float x, float y) const { return fmaxf(x, y); } static __device__ float id() { return -INFINITY; } };
+struct OpAddF { __device__ float operator()(float x, float y) const { return x + y; } static __device__ float id() { return 0.f; } };
+struct OpMaxD { __device__ double operator()(double x, double y) const { return fmax(x, y); } static __device__ double id() { return -INFINITY; } };
+struct OpAddD { __device__ double operator()(double x, double y) const { return x + y; } static __device__ double id() { return 0.0; } };
+template <class T, class Op>
+__device__ __forceinline__ T wave_reduce(T v, Op op) { return lane_value(wave_scan(v, op), 63); }
+__device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMaxF()); }
+__device__ __forceinline__ float wave_sum(float v) { return wave_reduce(v, OpAddF()); }
+__device__ __forceinline__ double wave_max(double v) { return wave_reduce(v, OpMaxD()); }
+__device__ __forceinline__ double wave_sum(double v) { return wave_reduce(v, OpAddD()); }
+
+// Block-wide reductions over kThreads threads of two values at once; results go to every thread.
+// `sh` holds two banks of 2*kWaves slots used alternately (`bank` flips on every call), so one
+// barrier per reduction is enough: a wave can only be two reductions ahead of another one after
+// that one has passed the barrier in between, i.e. after it has finished reading the bank.
+// Fixed order: the wave scan above, then waves 0..7.
+template <class T, class OpA, class OpB>
+__device__ __forceinline__ void block_reduce2(T& a, T& b, T* sh, int& bank, OpA opa, OpB opb)
 {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    a = wave_scan(a, opa);
+    b = wave_scan(b, opb);
+    T* s = sh + bank * 2 * kWaves;
+    bank ^= 1;
+    if (lane == 63) { s[wave] = a; s[kWaves + wave] = b; }
+    __syncthreads();
+    a = s[0];
+    b = s[kWaves];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-    return v;
+    for (int w = 1; w < kWaves; ++w) { a = opa(a, s[w]); b = opb(b, s[kWaves + w]); }
 }
 
-// Block-wide reductions over kThreads threads; `sh` has >= 4 slots; the result
-// is returned to every thread.
-#define RAPID_BLOCK_REDUCE(NAME, T, WAVE_OP, COMBINE)                      \
-    __device__ __forceinline__ T NAME(T v, T* sh)                          \
-    {                                                                      \
-        v = WAVE_OP(v);                                                    \
-        __syncthreads();                                                   \
-        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;             \
-        __syncthreads();                                                   \
-        T r = sh[0];                                                       \
-        for (int w = 1; w < kThreads / 64; ++w) r = COMBINE(r, sh[w]);     \
-        return r;                                                          \
-    }
-#define RAPID_ADD(a, b) ((a) + (b))
-RAPID_BLOCK_REDUCE(block_max, float, wave_max, fmaxf)
-RAPID_BLOCK_REDUCE(block_sum, float, wave_sum, RAPID_ADD)
-RAPID_BLOCK_REDUCE(block_max, double, wave_max, fmax)
-RAPID_BLOCK_REDUCE(block_sum, double, wave_sum, RAPID_ADD)
-
-// Four consecutive logits of a row starting at index i (i % 4 == 0); entries at or
-// past V come back as -inf.  `vec` says the row base is 16-byte aligned.
-__device__ __forceinline__ floatx4 load4(const float* row, int i, int V, bool vec)
+// Four consecutive logits of a row starting at index i (i % 4 == 0); entries at or past V
+// come back as -inf.  `vec` says the row base is 16-byte aligned (V a multiple of 4 keeps all
+// rows aligned; otherwise the loads are scalar, which is slower but reads the same values).
+__device__ __attribute__((noinline)) floatx4 load4_edge(const float* row, int64_t i, int V)
 {
     floatx4 r = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    if (vec && i + 3 < V) return *reinterpret_cast<const floatx4*>(row + i);
-#pragma unroll
     for (int j = 0; j < 4; ++j)
         if (i + j < V) r[j] = row[i + j];
     return r;
+}
+__device__ __forceinline__ floatx4 load4(const float* row, int64_t i, int V, bool vec)
+{
+    if (__builtin_expect(vec && i + 3 < V, 1)) return *reinterpret_cast<const floatx4*>(row + i);
+    return load4_edge(row, i, V);
 }
 
 // Drafts of sequence b; device data, so clamped to the range the buffers were sized for.
@@ -101,15 +163,22 @@ __device__ __forceinline__ int seq_gamma(const AcceptLaunch& a, int b)
     return a.gammas ? min(max(a.gammas[b], 0), a.gmax) : a.gmax;
 }
 
+// ---------------------------------------------------------------- workspace
 struct Ws {
-    float2* st_t;     // [B][gmax+1][nch]  (raw max, sum exp((z-max)/T))
-    float2* st_d;     // [B][gmax][nch]
-    float2* st_h;     // [B][gmax][nch]    (max d, sum exp(d - max d)), d relative to the target row max / T
-    double* rows;     // [B][gmax+1][8]: zmax_t, lse_p, zmax_d, lse_q, lse_h, 1/S_h (= max p_hat), -, -
-    double* wsum;     // [B][nch*kSubs][2]: per 256 entries, sum of residual weights and sum of p (fallback)
+    int32_t* status;  // [64]: [0] positions rejected because the draft id was outside [0, V)
+                      //       [1] exchange waits that gave up and recomputed the missing slice
+    u64* slot_t;      // [B][gmax+1][wmax]  (raw max, sum exp((z-max)/T)) per slice of a target row
+    u64* slot_d;      // [B][gmax][wmax]
+    u64* slot_h;      // [B][gmax][wmax]    (max d, sum exp2(d - max)), d in log2 units relative to zmax_t/T
+    u64* slot_b;      // [B][w2][6]         fp64 exchange words of accept_draw_row
+    int32_t* arrive;  // [B][gmax+1]        workgroups of a row that have published everything
+    double* rows;     // [B][gmax+1][4]: zmax_t, zmax_d (raw maxima, exact)
     int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
-    int nch;          // chunks of kChunk entries (st_h, wsum)
-    int nch_t, nch_d; // chunks of st_t / st_d: nch, or the caller's when the statistics come from outside
+    int wmax;         // slots per row (slices of the smallest slice size)
+    int w2;           // workgroups per sequence in accept_draw_row
+    size_t n_empty;   // u64 words from slot_t that start "empty"
+    size_t n_zero;    // int32 words from status / arrive that start at zero (two ranges)
+    size_t bytes;
 };
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -117,210 +186,446 @@ __host__ __device__ inline size_t align256(size_t x) { return (x + 255) / 256 * 
 __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
 {
     Ws w;
-    w.nch = (V + kChunk - 1) / kChunk;
-    w.nch_t = w.nch_d = w.nch;
+    const int gd = gmax > 0 ? gmax : 1;
+    w.wmax = (V + kMinSlice - 1) / kMinSlice;
+    w.w2 = (V + kDrawSlice - 1) / kDrawSlice;
     char* p = static_cast<char*>(base);
-    w.st_t = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax + 1) * w.nch * sizeof(float2));
-    w.st_d = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
-    w.st_h = reinterpret_cast<float2*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * w.nch * sizeof(float2));
-    w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 8 * sizeof(double));
-    w.wsum = reinterpret_cast<double*>(p); p += align256((size_t)B * w.nch * kSubs * 2 * sizeof(double));
-    w.flags = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * (gmax > 0 ? gmax : 1) * sizeof(int32_t));
+    w.status = reinterpret_cast<int32_t*>(p); p += 256;
+    w.arrive = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * (gmax + 1) * sizeof(int32_t));
+    w.n_zero = (size_t)(p - static_cast<char*>(base)) / sizeof(int32_t);
+    char* e0 = p;
+    w.slot_t = reinterpret_cast<u64*>(p); p += align256((size_t)B * (gmax + 1) * w.wmax * sizeof(u64));
+    w.slot_d = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * sizeof(u64));
+    w.slot_h = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * sizeof(u64));
+    w.slot_b = reinterpret_cast<u64*>(p); p += align256((size_t)B * w.w2 * 6 * sizeof(u64));
+    w.n_empty = (size_t)(p - e0) / sizeof(u64);
+    w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 4 * sizeof(double));
+    w.flags = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * gd * sizeof(int32_t));
+    w.bytes = (size_t)(p - static_cast<char*>(base));
     return w;
 }
 
-// ---------------------------------------------------------------- K1
-__global__ void __launch_bounds__(kThreads) accept_row_stats(AcceptLaunch a, Ws ws)
+__global__ void __launch_bounds__(256) accept_init(Ws ws)
 {
-    __shared__ float sh[8];
-    const int ch = blockIdx.x, y = blockIdx.y, b = blockIdx.z;
-    const int g = seq_gamma(a, b);
-    const bool is_t = y <= a.gmax;
-    const int k = is_t ? y : y - (a.gmax + 1);
-    if (is_t ? (k > g) : (k >= g)) return;
-    if (is_t ? a.ext_t != nullptr : a.ext_d != nullptr) return;    // this side's statistics were supplied
-    const float* row = is_t ? a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V
-                            : a.zd + ((int64_t)b * a.gmax + k) * a.V;
-    const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15) == 0);
-    floatx4 x[kVec];
-    float m = -INFINITY;
-#pragma unroll
-    for (int v = 0; v < kVec; ++v) {
-        x[v] = load4(row, ch * kChunk + (v * kThreads + threadIdx.x) * 4, a.V, vec);
-        m = fmaxf(m, fmaxf(fmaxf(x[v][0], x[v][1]), fmaxf(x[v][2], x[v][3])));
-    }
-    m = block_max(m, sh);
-    float s = 0.f;
-    if (m > -INFINITY) {
-#pragma unroll
-        for (int v = 0; v < kVec; ++v)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) s += fexp((x[v][j] - m) * a.inv_T);
-    }
-    s = block_sum(s, sh);
-    if (threadIdx.x == 0) {
-        float2* dst = is_t ? ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch
-                           : ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch;
-        dst[ch] = make_float2(m, s);
-    }
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, n = (size_t)gridDim.x * 256;
+    for (size_t j = i; j < ws.n_zero; j += n) ws.status[j] = 0;          // status and arrive are adjacent
+    for (size_t j = i; j < ws.n_empty; j += n) ws.slot_t[j] = kEmpty;    // all slot arrays are adjacent
 }
 
-// Combine per-chunk (max, sum) pairs of a row: returns the row max and
-// S = sum_i s_i exp((m_i - max) * inv_T) (inv_T = 1 when the maxima are already scaled).
-__device__ __forceinline__ void combine_row(const float2* st, int nch, double inv_T, double* shd,
-                                            double& M, double& S)
+// ---------------------------------------------------------------- exchange primitives
+__device__ __forceinline__ u64 slot_load(const u64* p)
 {
-    double m = -INFINITY;
-    for (int i = threadIdx.x; i < nch; i += kThreads) m = fmax(m, (double)st[i].x);
-    M = block_max(m, shd);
-    double s = 0.0;
-    for (int i = threadIdx.x; i < nch; i += kThreads) {
-        float2 v = st[i];
-        if (v.y > 0.f) s += (double)v.y * exp(((double)v.x - M) * inv_T);
-    }
-    S = block_sum(s, shd);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-
-// ---------------------------------------------------------------- K2
-// Row statistics of the target and the draft row, combined in fp32 by every workgroup
-// (enough for the elementwise pass; the decisions later use the fp64 combine of K3).
-__device__ __forceinline__ void combine_pair_f32(const float2* st_t, int nt, const float2* st_d, int nd, float inv_T,
-                                                 float* sh, float& Mt, float& lnSt, float& Md, float& lnSd)
+__device__ __forceinline__ void slot_store(u64* p, u64 v)
 {
-    float mt = -INFINITY, md = -INFINITY;
-    for (int i = threadIdx.x; i < nt; i += kThreads) mt = fmaxf(mt, st_t[i].x);
-    for (int i = threadIdx.x; i < nd; i += kThreads) md = fmaxf(md, st_d[i].x);
-    mt = wave_max(mt);
-    md = wave_max(md);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = mt; sh[4 + (threadIdx.x >> 6)] = md; }
-    __syncthreads();
-    Mt = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
-    Md = fmaxf(fmaxf(sh[4], sh[5]), fmaxf(sh[6], sh[7]));
-    float st = 0.f, sd = 0.f;
-    for (int i = threadIdx.x; i < nt; i += kThreads) {
-        float2 t = st_t[i];
-        if (t.y > 0.f) st += t.y * fexp((t.x - Mt) * inv_T);
-    }
-    for (int i = threadIdx.x; i < nd; i += kThreads) {
-        float2 d = st_d[i];
-        if (d.y > 0.f) sd += d.y * fexp((d.x - Md) * inv_T);
-    }
-    st = wave_sum(st);
-    sd = wave_sum(sd);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = st; sh[4 + (threadIdx.x >> 6)] = sd; }
-    __syncthreads();
-    lnSt = __logf((sh[0] + sh[1]) + (sh[2] + sh[3]));
-    lnSd = __logf((sh[4] + sh[5]) + (sh[6] + sh[7]));
+    if (v == kEmpty) v ^= 1ull;                      // never publish the "empty" pattern itself
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-
-__global__ void __launch_bounds__(kThreads) accept_shifted_stats(AcceptLaunch a, Ws ws)
+__device__ __forceinline__ u64 pack2f(float a, float b)
 {
-    __shared__ float sh[8];
-    const int ch = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
-    const int g = seq_gamma(a, b);
-    if (k >= g) return;
-    const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + k) * a.V;
-    const float* zd = a.zd + ((int64_t)b * a.gmax + k) * a.V;
-    const bool vec = ((reinterpret_cast<uintptr_t>(zt) & 15) == 0) && ((reinterpret_cast<uintptr_t>(zd) & 15) == 0);
-    floatx4 x[kVec], y[kVec];                     // in flight while the row statistics combine
-#pragma unroll
-    for (int v = 0; v < kVec; ++v) {
-        const int i0 = ch * kChunk + (v * kThreads + threadIdx.x) * 4;
-        x[v] = load4(zt, i0, a.V, vec);
-        y[v] = load4(zd, i0, a.V, vec);
-    }
-    float zmax_t, lnS_t, zmax_d, lnS_d;
-    combine_pair_f32(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch_t, ws.nch_t,
-                     ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch_d, ws.nch_d, a.inv_T, sh, zmax_t, lnS_t, zmax_d, lnS_d);
-    float m = -INFINITY;
-#pragma unroll
-    for (int v = 0; v < kVec; ++v)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float at = (x[v][j] - zmax_t) * a.inv_T;          // z/T relative to the row max
-            float ad = (y[v][j] - zmax_d) * a.inv_T;
-            float p = fexp(at - lnS_t), q = fexp(ad - lnS_d);
-            // entries past V were loaded as -inf: at = -inf, p = q = 0 -> d = -inf
-            x[v][j] = fmaf(a.eta, q - p, at);
-            m = fmaxf(m, x[v][j]);
+    return (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
+}
+__device__ __forceinline__ float lo_f(u64 v) { return __uint_as_float((uint32_t)v); }
+__device__ __forceinline__ float hi_f(u64 v) { return __uint_as_float((uint32_t)(v >> 32)); }
+__device__ __forceinline__ u64 pack_d(double d) { return (u64)__double_as_longlong(d); }
+__device__ __forceinline__ double unpack_d(u64 v) { return __longlong_as_double((long long)v); }
+
+// Compact fp64 exponential (about twenty instructions, inlined where used): exp(x) with ~2e-16
+// relative error for x <= 700; anything below -745 (also -inf and NaN) gives 0.  The decisions
+// need fp64 but each workgroup runs its code exactly once, so instruction count matters more
+// here than in a loop: the library routine is several times longer.
+__device__ __forceinline__ double exp_c(double x)
+{
+    x = fmax(x, -746.0);
+    const double k = rint(x * 1.4426950408889634);
+    double r = fma(k, -6.93147180369123816490e-01, x);        // k ln2 in two parts
+    r = fma(k, -1.90821492927058770002e-10, r);
+    double p = 1.0 / 6227020800.0;                           // Taylor to r^13 / 13!, |r| <= 0.347
+    p = fma(p, r, 1.0 / 479001600.0);
+    p = fma(p, r, 1.0 / 39916800.0);
+    p = fma(p, r, 1.0 / 3628800.0);
+    p = fma(p, r, 1.0 / 362880.0);
+    p = fma(p, r, 1.0 / 40320.0);
+    p = fma(p, r, 1.0 / 5040.0);
+    p = fma(p, r, 1.0 / 720.0);
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)k);
+}
+// Wave 0: poll the slots addr(lo) .. addr(hi - 1) into dst[lo .. hi) until none is empty or
+// `wait_ticks` have passed; *nmiss = slots still empty (left as kEmpty in dst).
+template <class Addr>
+__device__ __forceinline__ void poll_into(Addr addr, int lo, int hi, u64* dst, int* nmiss, int64_t wait_ticks)
+{
+    const int lane = threadIdx.x;
+    const int64_t t0 = (int64_t)wall_clock64();
+    int miss = 0;
+    for (int i0 = lo; i0 < hi; i0 += 64) {
+        const int i = i0 + lane;
+        u64 v = kEmpty;
+        bool pending = i < hi;
+        for (;;) {
+            if (pending) {
+                v = slot_load(addr(i));
+                pending = v == kEmpty;
+            }
+            if (!__any(pending)) break;
+            if ((int64_t)wall_clock64() - t0 >= wait_ticks) break;
+            __builtin_amdgcn_s_sleep(2);
         }
-    m = block_max(m, sh);
-    float s = 0.f;
-    if (m > -INFINITY) {
-#pragma unroll
-        for (int v = 0; v < kVec; ++v)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) s += fexp(x[v][j] - m);
+        if (i < hi) dst[i] = v;
+        miss += __popcll(__ballot(pending));
     }
-    s = block_sum(s, sh);
-    if (threadIdx.x == 0) ws.st_h[((int64_t)b * a.gmax + k) * ws.nch + ch] = make_float2(m, s);
+    if (lane == 0) *nmiss = miss;
 }
 
-// ---------------------------------------------------------------- K3
-// One wave per (sequence, row): combine the row's per-chunk statistics in fp64 and
-// run the accept test of that row's drafted token.
-__device__ __forceinline__ void wave_combine(const float2* st, int nch, double inv_T, double& M, double& S)
+// ---------------------------------------------------------------- accept_rows: per-slice arithmetic
+// The statistics of a slice are written once, as templates over the way a thread gets at its
+// NV float4 of a row: from registers (the workgroup's own slice) or from memory (a slice whose
+// publication did not arrive in time).  Same operations in the same order either way; this file
+// is compiled without implicit multiply-add contraction so that the two instantiations round alike.
+// UNROLL: the register path unrolls (its arrays need constant indices); the memory path keeps its
+// loops rolled, it is code that normally never runs and should stay small.
+template <int NV, bool UNROLL, class GetT, class GetD>
+__device__ __forceinline__ void slice_stats(GetT gt, GetD gd, bool do_t, bool do_d, float c, float* sh, int& bank,
+                                            float& mt, float& st, float& md, float& sd)
+{
+    mt = -INFINITY;
+    md = -INFINITY;
+    if (do_t)
+#pragma unroll UNROLL ? NV : 1
+        for (int v = 0; v < NV; ++v) {
+            const floatx4 x = gt(v);
+            mt = fmaxf(mt, fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])));
+        }
+    if (do_d)
+#pragma unroll UNROLL ? NV : 1
+        for (int v = 0; v < NV; ++v) {
+            const floatx4 y = gd(v);
+            md = fmaxf(md, fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])));
+        }
+    block_reduce2(mt, md, sh, bank, OpMaxF(), OpMaxF());
+    st = 0.f;
+    sd = 0.f;
+    if (do_t && mt > -INFINITY)
+#pragma unroll UNROLL ? NV : 1
+        for (int v = 0; v < NV; ++v) {
+            const floatx4 x = gt(v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st += fexp2((x[j] - mt) * c);
+        }
+    if (do_d && md > -INFINITY)
+#pragma unroll UNROLL ? NV : 1
+        for (int v = 0; v < NV; ++v) {
+            const floatx4 y = gd(v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sd += fexp2((y[j] - md) * c);
+        }
+    block_reduce2(st, sd, sh, bank, OpAddF(), OpAddF());
+}
+
+// Row normalisers in the form the elementwise pass uses (log2 units).
+struct PairNorm { float Mt, l2St, Md, l2Sd; };
+
+// d = z/T + eta (q - p) of one entry, in log2 units relative to zmax_t/T.  Entries past V were
+// loaded as -inf: p = q = 0 and d = -inf.
+__device__ __forceinline__ float shifted(float zt, float zd, const PairNorm& r, float c, float eta_l2)
+{
+    const float at = (zt - r.Mt) * c;
+    const float p = fexp2(at - r.l2St);
+    const float q = fexp2((zd - r.Md) * c - r.l2Sd);
+    return fmaf(eta_l2, q - p, at);
+}
+
+// (max d, sum exp2(d - max)) of a slice; d_first(v) yields d of the thread's v-th float4 (the register
+// path also stores it), d_again(v) yields it again (from the registers, or recomputed: same value).
+template <int NV, bool UNROLL, class GetFirst, class GetAgain>
+__device__ __forceinline__ void shifted_stats(GetFirst d_first, GetAgain d_again, float* sh, int& bank, float& mh,
+                                              float& shs)
+{
+    mh = -INFINITY;
+    float unused = -INFINITY;
+#pragma unroll UNROLL ? NV : 1
+    for (int v = 0; v < NV; ++v) {
+        const floatx4 d = d_first(v);
+        mh = fmaxf(mh, fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3])));
+    }
+    block_reduce2(mh, unused, sh, bank, OpMaxF(), OpMaxF());
+    shs = 0.f;
+    unused = 0.f;
+    if (mh > -INFINITY)
+#pragma unroll UNROLL ? NV : 1
+        for (int v = 0; v < NV; ++v) {
+            const floatx4 d = d_again(v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) shs += fexp2(d[j] - mh);
+        }
+    block_reduce2(shs, unused, sh, bank, OpAddF(), OpAddF());
+}
+
+// Wave 0: combine n (max, sum) pairs, maxima raw logits, sums of exp((z - max)/T):
+// M = max, S = sum_i s_i 2^((m_i - M) c); fp32, fixed order.  Result valid in every lane of wave 0.
+template <class Pair>
+__device__ __forceinline__ void wave_combine_f32(Pair pair, int n, float c, float& M, float& l2S)
+{
+    const int lane = threadIdx.x & 63;
+    float m = -INFINITY;
+    for (int i = lane; i < n; i += 64) m = fmaxf(m, pair(i).x);
+    M = wave_max(m);
+    float s = 0.f;
+    for (int i = lane; i < n; i += 64) {
+        const float2 v = pair(i);
+        if (v.y > 0.f) s += v.y * fexp2((v.x - M) * c);
+    }
+    l2S = __log2f(wave_sum(s));
+}
+// The same in fp64 (decisions); `scale` multiplies the difference of maxima (1/T for raw logits,
+// ln 2 for maxima kept in log2 units).
+template <class Pair>
+__device__ __forceinline__ void wave_combine_f64(Pair pair, int n, double scale, double& M, double& S)
 {
     const int lane = threadIdx.x & 63;
     double m = -INFINITY;
-    for (int i = lane; i < nch; i += 64) m = fmax(m, (double)st[i].x);
+    for (int i = lane; i < n; i += 64) m = fmax(m, (double)pair(i).x);
     M = wave_max(m);
     double s = 0.0;
-    for (int i = lane; i < nch; i += 64) {
-        float2 v = st[i];
-        if (v.y > 0.f) s += (double)v.y * exp(((double)v.x - M) * inv_T);
+    for (int i = lane; i < n; i += 64) {
+        const float2 v = pair(i);
+        if (v.y > 0.f) s += (double)v.y * exp_c(((double)v.x - M) * scale);
     }
     S = wave_sum(s);
 }
 
-__global__ void __launch_bounds__(64) accept_decide(AcceptLaunch a, Ws ws)
+struct LdsA {
+    float red[4 * kWaves];
+    PairNorm norm;
+    int last;
+    int nmiss;
+    u64 slots[];          // 2 W words: target slices, draft slices; later the W shifted slices
+};
+
+// ---------------------------------------------------------------- accept_rows
+// One workgroup per work item (sequence b, row k, slice w), slice index fastest in dispatch order, so
+// the slices of one row pair are worked on by different workgroups at about the same time.
+template <int NV>
+__global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws, int W, int n_items)
 {
-    const int k = blockIdx.x, b = blockIdx.y;
-    const int g = seq_gamma(a, b);
-    if (k > g) return;
-    // the drafted token's two logits are fetched while the statistics combine
-    int x = -1;
-    float zx_t = 0.f, zx_d = 0.f;
-    if (k < g) {
-        x = a.tokens[(int64_t)b * a.gmax + k];
-        if (x >= 0 && x < a.V) {
-            zx_t = a.zt[((int64_t)b * (a.gmax + 1) + k) * a.V + x];
-            zx_d = a.zd[((int64_t)b * a.gmax + k) * a.V + x];
+    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+    LdsA& lds = *reinterpret_cast<LdsA*>(smem_raw);
+    constexpr int kSlice = kThreads * 4 * NV;
+    const int tid = threadIdx.x;
+    const int V = a.V, rows = a.gmax + 1;
+    int bank = 0;
+    const float c = a.inv_T * kLog2e, eta_l2 = a.eta * kLog2e;
+
+    // Item id -> (w, k, b); g = drafts of its sequence (a device value, read one item ahead).
+    auto row_t = [&](int b, int k) { return a.zt + ((int64_t)b * rows + k) * V; };
+    auto row_d = [&](int b, int k) { return a.zd + ((int64_t)b * a.gmax + k) * V; };
+
+    // Issue the loads of item `id` into x / y (nothing for rows past the sequence's drafts).
+    auto issue = [&](int id, int g, floatx4 (&x)[NV], floatx4 (&y)[NV]) {
+        const int w = id % W, k = (id / W) % rows, b = id / (W * rows);
+        if (k > g) return;
+        const bool pair = k < g;
+        const float* zt = row_t(b, k);
+        const float* zd = pair ? row_d(b, k) : nullptr;
+        const bool vec_t = (reinterpret_cast<uintptr_t>(zt) & 15) == 0;
+        const bool vec_d = (reinterpret_cast<uintptr_t>(zd) & 15) == 0;
+        if (vec_t && (!pair || vec_d) && (int64_t)(w + 1) * kSlice <= V) {
+            // the whole slice exists and both rows are aligned: plain 128-bit loads (uniform branch)
+            const floatx4* pt = reinterpret_cast<const floatx4*>(zt + (int64_t)w * kSlice) + tid;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) x[v] = pt[v * kThreads];
+            if (pair) {
+                const floatx4* pd = reinterpret_cast<const floatx4*>(zd + (int64_t)w * kSlice) + tid;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) y[v] = pd[v * kThreads];
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) x[v] = load4(zt, (int64_t)w * kSlice + (v * kThreads + tid) * 4, V, vec_t);
+            if (pair) {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) y[v] = load4(zd, (int64_t)w * kSlice + (v * kThreads + tid) * 4, V, vec_d);
+            }
         }
-    }
-    double Mt, St, Md = 0, Sd = 1, Mh = 0, Sh = 1;
-    wave_combine(ws.st_t + ((int64_t)b * (a.gmax + 1) + k) * ws.nch_t, ws.nch_t, a.inv_T_exact, Mt, St);
-    if (k < g) {
-        wave_combine(ws.st_d + ((int64_t)b * a.gmax + k) * ws.nch_d, ws.nch_d, a.inv_T_exact, Md, Sd);
-        wave_combine(ws.st_h + ((int64_t)b * a.gmax + k) * ws.nch, ws.nch, 1.0, Mh, Sh);
-    }
-    if (threadIdx.x != 0) return;
-    double* r = ws.rows + ((int64_t)b * (a.gmax + 1) + k) * 8;
-    const double lnS_t = log(St), lnS_d = log(Sd), lse_h = Mh + log(Sh), pmax = 1.0 / Sh;
-    r[0] = Mt;                                   // raw max of the target row
-    r[1] = lnS_t;                                // lse_p = r[0]/T + r[1]
-    r[2] = Md;
-    r[3] = lnS_d;
-    r[4] = lse_h;                                // lse_h = r[0]/T + r[4]
-    r[5] = pmax;                                 // max p_hat
-    if (k >= g) return;
-    double rho = 0.0;
-    bool ok = false;
-    if (x >= 0 && x < a.V) {
-        const double invT = a.inv_T_exact;
-        double at = ((double)zx_t - Mt) * invT;
-        double ad = ((double)zx_d - Md) * invT;
-        double p = exp(at - lnS_t), q = exp(ad - lnS_d);
-        double ph = exp(at + (double)a.eta * (q - p) - lse_h);
-        if (ph < (double)a.tail_alpha * pmax) ph = p;
-        rho = q > 0.0 ? ph / q : INFINITY;
-        double u = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + k];
-        ok = u <= fmin(1.0, rho);
-    }
-    if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
-    ws.flags[(int64_t)b * a.gmax + k] = ok ? 1 : 0;
+    };
+
+    // Everything after the loads of one item.
+    auto process = [&](int id, int g, floatx4 (&x)[NV], floatx4 (&y)[NV]) {
+        const int w = id % W, k = (id / W) % rows, b = id / (W * rows);
+        if (k > g) return;
+        STAMP_AT(id, 1);
+        const bool pair = k < g;                              // row g has a target row only (the bonus position)
+        const float* zt = row_t(b, k);
+        const float* zd = pair ? row_d(b, k) : nullptr;
+        const bool vec_t = (reinterpret_cast<uintptr_t>(zt) & 15) == 0;
+        const bool vec_d = (reinterpret_cast<uintptr_t>(zd) & 15) == 0;
+        const bool own_t = a.ext_t == nullptr, own_d = pair && a.ext_d == nullptr;
+        u64* slot_t = ws.slot_t + ((int64_t)b * rows + k) * ws.wmax;
+        u64* slot_d = ws.slot_d + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax;
+        u64* slot_h = ws.slot_h + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax;
+        auto reg_t = [&](int v) { return x[v]; };
+        auto reg_d = [&](int v) { return y[v]; };
+        // slice s of either row straight from memory (a slice another workgroup owns)
+        auto mem_slice = [&](const float* row, bool vec, int s) {
+            return [row, vec, s, tid, V](int v) { return load4(row, (int64_t)s * kSlice + (v * kThreads + tid) * 4, V, vec); };
+        };
+
+        // ---- statistics of the own slice
+        if (own_t || own_d) {
+            float mt, st, md, sd;
+            slice_stats<NV, true>(reg_t, reg_d, own_t, own_d, c, lds.red, bank, mt, st, md, sd);
+            if (tid == 0) {
+                if (own_t) slot_store(slot_t + w, pack2f(mt, st));
+                if (own_d) slot_store(slot_d + w, pack2f(md, sd));
+            }
+        }
+        STAMP_AT(id, 2);
+
+        // ---- publications of all slices of the row (pair): lds.slots[0..W) target, [W..2W) draft.
+        // A slice that stays empty past the bound is computed here (and published for the others).
+        u64* got = lds.slots;
+        auto gather = [&](bool need_t, bool need_d) {
+            const int lo = need_t ? 0 : W, hi = need_d ? 2 * W : W;
+            if (tid < 64) poll_into([&](int i) { return i < W ? slot_t + i : slot_d + (i - W); }, lo, hi, got, &lds.nmiss,
+                                    a.wait_ticks);
+            __syncthreads();
+            if (__builtin_expect(lds.nmiss != 0, 0)) {
+                for (int s = 0; s < W; ++s) {
+                    const bool miss_t = need_t && got[s] == kEmpty, miss_d = need_d && got[W + s] == kEmpty;
+                    if (!miss_t && !miss_d) continue;
+                    float mt, st, md, sd;
+                    slice_stats<NV, false>(mem_slice(zt, vec_t, s), mem_slice(zd, vec_d, s), miss_t, miss_d, c, lds.red, bank, mt, st, md, sd);
+                    if (tid == 0) {
+                        if (miss_t) { got[s] = pack2f(mt, st); slot_store(slot_t + s, got[s]); }
+                        if (miss_d) { got[W + s] = pack2f(md, sd); slot_store(slot_d + s, got[W + s]); }
+                        atomicAdd(ws.status + 1, 1);
+                    }
+                    __syncthreads();
+                }
+            }
+        };
+        // (max, sum) pair i of the target / draft row: a slot, or the caller's statistics
+        const float2* ext_t = a.ext_t ? reinterpret_cast<const float2*>(a.ext_t) + ((int64_t)b * rows + k) * a.nch_t : nullptr;
+        const float2* ext_d = (pair && a.ext_d) ? reinterpret_cast<const float2*>(a.ext_d) + ((int64_t)b * a.gmax + k) * a.nch_d : nullptr;
+        auto pair_t = [&](int i) { return ext_t ? ext_t[i] : make_float2(lo_f(got[i]), hi_f(got[i])); };
+        auto pair_d = [&](int i) { return ext_d ? ext_d[i] : make_float2(lo_f(got[W + i]), hi_f(got[W + i])); };
+        const int n_t = ext_t ? a.nch_t : W, n_d = ext_d ? a.nch_d : W;
+
+        if (pair) {
+            gather(own_t, own_d);
+            STAMP_AT(id, 3);
+            if (tid < 64) {
+                PairNorm r;
+                wave_combine_f32(pair_t, n_t, c, r.Mt, r.l2St);
+                wave_combine_f32(pair_d, n_d, c, r.Md, r.l2Sd);
+                if (tid == 0) lds.norm = r;
+            }
+            __syncthreads();
+            const PairNorm r = lds.norm;
+            // ---- d for the own slice (kept in x), its statistics
+            float mh, shs;
+            auto d_first = [&](int v) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x[v][j] = shifted(x[v][j], y[v][j], r, c, eta_l2);
+                return x[v];
+            };
+            shifted_stats<NV, true>(d_first, reg_t, lds.red, bank, mh, shs);
+            if (tid == 0) slot_store(slot_h + w, pack2f(mh, shs));
+            STAMP_AT(id, 4);
+        }
+
+        // ---- the last workgroup to arrive at this row decides it
+        if (tid == 0) lds.last = atomicAdd(ws.arrive + (int64_t)b * rows + k, 1) == W - 1;
+        __syncthreads();
+        STAMP_AT(id, 5);
+        if (lds.last) {
+            // Wave 0 first fetches the drafted token's two logits (a dependent chain that overlaps the polls).
+            int xtok = -1;
+            float zx_t = 0.f, zx_d = 0.f;
+            if (pair && tid < 64) {
+                xtok = a.tokens[(int64_t)b * a.gmax + k];
+                if (xtok >= 0 && xtok < V) { zx_t = zt[xtok]; zx_d = zd[xtok]; }
+            }
+            u64* got_h = lds.slots + 2 * W;
+            if (!pair) {
+                gather(own_t, false);                         // (a pair's workgroups all gathered above)
+            } else {
+                if (tid < 64) poll_into([&](int i) { return slot_h + i; }, 0, W, got_h, &lds.nmiss, a.wait_ticks);
+                __syncthreads();
+                if (__builtin_expect(lds.nmiss != 0, 0)) {
+                    const PairNorm r = lds.norm;
+                    for (int s = 0; s < W; ++s) {
+                        if (got_h[s] != kEmpty) continue;
+                        auto gt = mem_slice(zt, vec_t, s);
+                        auto gd = mem_slice(zd, vec_d, s);
+                        auto d_mem = [&](int v) {
+                            floatx4 t4 = gt(v);
+                            const floatx4 d4 = gd(v);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) t4[j] = shifted(t4[j], d4[j], r, c, eta_l2);
+                            return t4;
+                        };
+                        float mh, shs;
+                        shifted_stats<NV, false>(d_mem, d_mem, lds.red, bank, mh, shs);
+                        if (tid == 0) { got_h[s] = pack2f(mh, shs); slot_store(slot_h + s, got_h[s]); atomicAdd(ws.status + 1, 1); }
+                        __syncthreads();
+                    }
+                }
+            }
+            STAMP_AT(id, 6);
+            if (tid < 64) {
+                // one wave: fp64 combine of the row's statistics and the accept test of its drafted token
+                double Mt, St, Md = 0, Sd = 1, Mh = 0, Sh = 1;
+                wave_combine_f64(pair_t, n_t, a.inv_T_exact, Mt, St);
+                if (pair) {
+                    wave_combine_f64(pair_d, n_d, a.inv_T_exact, Md, Sd);
+                    auto pair_h = [&](int i) { return make_float2(lo_f(got_h[i]), hi_f(got_h[i])); };
+                    wave_combine_f64(pair_h, W, kLn2, Mh, Sh);
+                }
+                if (tid == 0) {
+                    double* rec = ws.rows + ((int64_t)b * rows + k) * 4;
+                    rec[0] = Mt;                             // raw maxima: exact, reused by the draw
+                    rec[1] = Md;
+                    if (pair) {
+                        double rho = 0.0;
+                        bool ok = false;
+                        if (xtok >= 0 && xtok < V) {
+                            // p = e^at / St, q = e^ad / Sd, p_hat = e^(at + eta (q - p) - Mh ln2) / Sh, max p_hat = 1 / Sh
+                            const double invT = a.inv_T_exact;
+                            const double at = ((double)zx_t - Mt) * invT;
+                            const double p = exp_c(at) / St, q = exp_c(((double)zx_d - Md) * invT) / Sd;
+                            double ph = exp_c(at + (double)a.eta * (q - p) - Mh * kLn2) / Sh;
+                            if (ph < (double)a.tail_alpha / Sh) ph = p;
+                            rho = q > 0.0 ? ph / q : INFINITY;
+                            const double u = (double)a.uniforms[(int64_t)b * rows + k];
+                            ok = u <= fmin(1.0, rho);
+                        } else {
+                            atomicAdd(ws.status + 0, 1);      // id outside the vocabulary: rejected, and counted
+                        }
+                        if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
+                        ws.flags[(int64_t)b * a.gmax + k] = ok ? 1 : 0;
+                    }
+                }
+            }
+            STAMP_AT(id, 7);
+        }
+        __syncthreads();                                      // lds.slots / lds.norm are reused by the next item
+    };
+
+    floatx4 x[NV], y[NV];
+    const int id = blockIdx.x;
+    if (id >= n_items) return;
+    const int g = seq_gamma(a, id / (W * rows));
+    STAMP_AT(id, 0);
+    issue(id, g, x, y);
+    process(id, g, x, y);
 }
 
 // Number of accepted drafts: index of the first failed accept test, or g.
@@ -332,210 +637,269 @@ __device__ __forceinline__ int first_reject(const Ws& ws, int b, int gmax, int g
     return n;
 }
 
-// Draw weight of vocabulary entry v of row n (fp64): the residual
-// max(p - p_hat', p - q, 0) when n < g, p itself for the bonus row n = g.
-struct RowCtx {
-    const float* zt;
-    const float* zd;
-    double zmax_t, lnS_t, zmax_d, lnS_d, lse_h_rel, tail_thr, eta, invT;
-    bool bonus;
+// ---------------------------------------------------------------- accept_draw_row (fp64)
+// Thread t of workgroup w owns the NE consecutive entries  w*512*NE + t*NE + i  (i = 0..NE-1), so
+// vocabulary order inside a workgroup is thread order.
+//
+// Phase 1: e_t = exp((z - zmax)/T), e_d likewise; sums -> p = e_t/S_t, q = e_d/S_d.
+// Phase 2: f = e_t exp(eta (q - p)) (p_hat up to its normaliser); sum and max of f -> p_hat = f/S_h
+//          and the tail threshold alpha max p_hat.
+// Phase 3: the residual weights max(p - p_hat', p - q, 0) and p; their sums per slice.
+// The bonus row (all drafts accepted) draws from p: phase 1 only, weights e_t.
+struct DrawNorm { double iSt, iSd, iSh, thr, eta; };
+
+struct LdsB {
+    double red[4 * kWaves];
+    int nmiss;
+    int pick_lo, pick_hi;
+    u64 slots[];          // 2 W2 words: the two sums of every slice for the current phase
 };
-__device__ __forceinline__ RowCtx make_row_ctx(const AcceptLaunch& a, const Ws& ws, int b, int n, int g)
+
+// The three quantities of one entry that the phases are made of.
+__device__ __forceinline__ double draw_f(double et, double ed, const DrawNorm& nm)
 {
-    RowCtx c;
-    const double* r = ws.rows + ((int64_t)b * (a.gmax + 1) + n) * 8;
-    c.zt = a.zt + ((int64_t)b * (a.gmax + 1) + n) * a.V;
-    c.zd = n < g ? a.zd + ((int64_t)b * a.gmax + n) * a.V : nullptr;
-    c.zmax_t = r[0]; c.lnS_t = r[1]; c.zmax_d = r[2]; c.lnS_d = r[3]; c.lse_h_rel = r[4];
-    c.tail_thr = (double)a.tail_alpha * r[5];
-    c.eta = (double)a.eta;
-    c.invT = (double)a.inv_T_exact;
-    c.bonus = n >= g;
-    return c;
+    return et * exp_c(nm.eta * (ed * nm.iSd - et * nm.iSt));
 }
-__device__ __forceinline__ void weights(const RowCtx& c, int v, double& w, double& p)
+__device__ __forceinline__ double draw_weight(double et, double ed, const DrawNorm& nm, double& p)
 {
-    double at = ((double)c.zt[v] - c.zmax_t) * c.invT;
-    p = exp(at - c.lnS_t);
-    if (c.bonus) { w = p; return; }
-    double ad = ((double)c.zd[v] - c.zmax_d) * c.invT;
-    double q = exp(ad - c.lnS_d);
-    double ph = exp(at + c.eta * (q - p) - c.lse_h_rel);
-    if (ph < c.tail_thr) ph = p;
-    w = fmax(fmax(p - ph, p - q), 0.0);
+    p = et * nm.iSt;
+    const double q = ed * nm.iSd;
+    double ph = draw_f(et, ed, nm) * nm.iSh;
+    if (ph < nm.thr) ph = p;
+    return fmax(fmax(p - ph, p - q), 0.0);
+}
+// Accumulates entry (et, ed) into the two running values of `phase`; the entries of a thread are
+// taken in index order both by the register path and by the memory path.
+__device__ __forceinline__ void draw_accumulate(int phase, double et, double ed, const DrawNorm& nm, double& a0, double& a1)
+{
+    if (phase == 1) {
+        a0 += et;
+        a1 += ed;
+    } else if (phase == 2) {
+        const double f = draw_f(et, ed, nm);
+        a0 += f;
+        a1 = fmax(a1, f);
+    } else {
+        double p;
+        a0 += draw_weight(et, ed, nm, p);
+        a1 += p;
+    }
 }
 
-// ---------------------------------------------------------------- K4
-__global__ void __launch_bounds__(kThreads) accept_residual_sums(AcceptLaunch a, Ws ws)
+template <int NE>
+__global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, Ws ws, int W2)
 {
-    const int ch = blockIdx.x, b = blockIdx.y;
+    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+    LdsB& lds = *reinterpret_cast<LdsB*>(smem_raw);
+    constexpr int kSlice = kThreads * NE;
+    const int w = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    STAMP(8);
     const int g = seq_gamma(a, b);
     const int n = first_reject(ws, b, a.gmax, g);
-    if (ch == 0) {
-        // accepted drafts, then -1 (the draw fills slot n later)
-        for (int k = threadIdx.x; k <= a.gmax; k += kThreads)
-            a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
-        if (threadIdx.x == 0) a.n_accepted[b] = n;
+    const double u = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + a.gmax];
+    if (w == 0) {
+        // accepted drafts, then -1 (the draw fills slot n)
+        for (int k = tid; k <= a.gmax; k += kThreads)
+            if (k != n) a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
+        if (tid == 0) a.n_accepted[b] = n;
     }
-    RowCtx c = make_row_ctx(a, ws, b, n, g);
-    // one partial sum per wave: a run of 256 consecutive entries (the fp64 exponentials make
-    // this kernel ALU-heavy, so it uses four times more workgroups than the statistics kernels)
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i0 = (ch * kThreads + threadIdx.x) * 4;
-    double sw = 0.0, sp = 0.0;
+    const int V = a.V;
+    int bank = 0;
+    const bool bonus = n >= g;
+    const float* zt = a.zt + ((int64_t)b * (a.gmax + 1) + n) * V;
+    const float* zd = bonus ? nullptr : a.zd + ((int64_t)b * a.gmax + n) * V;
+    const bool vec_t = (reinterpret_cast<uintptr_t>(zt) & 15) == 0;
+    const bool vec_d = (reinterpret_cast<uintptr_t>(zd) & 15) == 0;
+    const double* rec = ws.rows + ((int64_t)b * (a.gmax + 1) + n) * 4;
+    const double Mt = rec[0], Md = rec[1], invT = a.inv_T_exact;
+
+    // own slice: e_t, e_d of the thread's entries, kept in registers for all phases
+    double et[NE], ed[NE];
+    const int64_t first = (int64_t)w * kSlice + (int64_t)tid * NE;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (i0 + j < a.V) {
-            double w, p;
-            weights(c, i0 + j, w, p);
-            sw += w;
-            sp += p;
+    for (int v = 0; v < NE / 4; ++v) {
+        const floatx4 t4 = load4(zt, first + v * 4, V, vec_t);
+        floatx4 d4 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (!bonus) d4 = load4(zd, first + v * 4, V, vec_d);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            et[v * 4 + j] = exp_c(((double)t4[j] - Mt) * invT);
+            ed[v * 4 + j] = bonus ? 0.0 : exp_c(((double)d4[j] - Md) * invT);
         }
     }
-    sw = wave_sum(sw);
-    sp = wave_sum(sp);
-    if (lane == 0) {
-        const int64_t sub = (int64_t)b * ws.nch * kSubs + ch * (kThreads / 64) + wave;
-        ws.wsum[sub * 2 + 0] = sw;
-        ws.wsum[sub * 2 + 1] = sp;
-    }
-}
+    STAMP(9);
+    DrawNorm nm{1.0, 0.0, 0.0, 0.0, (double)a.eta};
+    u64* my_slots = ws.slot_b + (int64_t)b * ws.w2 * 6;
 
-// ---------------------------------------------------------------- K5
-// Prefix sums over the kThreads threads of a block (fp64); `sh` has >= 4 slots.
-// Returns the exclusive prefix; `incl` gets the inclusive one and `total` the block
-// sum.  incl of thread j and the exclusive prefix of thread j+1 are the same
-// floating-point value, so "first prefix above t" has exactly one owner.
-__device__ __forceinline__ double block_scan(double v, double* sh, double& incl, double& total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    double iw = v;
+    // Reduction of word `word` (0 / 1) of the current phase over all slices, in a fixed order (the
+    // same in every workgroup): lanes take slices lane, lane + 64, ...; then the wave reduction.
+    auto all_sum = [&](int word) {
+        double s = 0.0;
+        for (int i = lane; i < W2; i += 64) s += unpack_d(lds.slots[2 * i + word]);
+        return wave_sum(s);
+    };
+    auto all_max = [&](int word) {
+        double s = -INFINITY;
+        for (int i = lane; i < W2; i += 64) s = fmax(s, unpack_d(lds.slots[2 * i + word]));
+        return wave_max(s);
+    };
+
+    const int nphase = bonus ? 1 : 3;
+    for (int phase = 1; phase <= nphase; ++phase) {
+        double a0 = 0.0, a1 = phase == 2 ? -INFINITY : 0.0;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        double y = __shfl_up(iw, o);
-        if (lane >= o) iw += y;
-    }
-    double ew = __shfl_up(iw, 1);
-    if (lane == 0) ew = 0.0;
-    __syncthreads();
-    if (lane == 63) sh[wave] = iw;
-    __syncthreads();
-    double off = 0.0, tot = 0.0;
-#pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) {
-        if (w < wave) off += sh[w];
-        tot += sh[w];
-    }
-    total = tot;
-    incl = off + iw;
-    return off + ew;
-}
-
-__global__ void __launch_bounds__(kThreads) accept_draw(AcceptLaunch a, Ws ws)
-{
-    __shared__ double shd[8];
-    __shared__ int pick_chunk, last_chunk, pick_lo, pick_hi;
-    __shared__ double chunk_base;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const int g = seq_gamma(a, b);
-    const int n = first_reject(ws, b, a.gmax, g);
-    RowCtx c = make_row_ctx(a, ws, b, n, g);
-    const int nsub = ws.nch * kSubs;             // partial sums of 256 entries, in vocabulary order
-    const double* cs = ws.wsum + (int64_t)b * nsub * 2;
-    if (tid == 0) { pick_chunk = -1; last_chunk = 0; pick_lo = 0x7fffffff; pick_hi = -1; }
-
-    // every thread owns `per` consecutive chunks
-    const int per = (nsub + kThreads - 1) / kThreads;
-    const int cbeg = min(tid * per, nsub), cend = min(cbeg + per, nsub);
-    double tw = 0.0, tp = 0.0;
-    for (int i = cbeg; i < cend; ++i) { tw += cs[i * 2]; tp += cs[i * 2 + 1]; }
-    double Wres, Wp, in_w, in_p;
-    const double ex_w = block_scan(tw, shd, in_w, Wres);
-    const double ex_p = block_scan(tp, shd, in_p, Wp);
-    const int col = Wres > 0.0 ? 0 : 1;          // empty residual: draw from p instead
-    const double W = col == 0 ? Wres : Wp;
-    const double t = (double)a.uniforms[(int64_t)b * (a.gmax + 1) + a.gmax] * W;
-
-    // chunk whose inclusive running sum first exceeds t (chunks in vocabulary order)
-    {
-        const double excl = col == 0 ? ex_w : ex_p, incl = col == 0 ? in_w : in_p;
-        int lastpos = -1;
-        for (int i = cbeg; i < cend; ++i) if (cs[i * 2 + col] > 0.0) lastpos = i;
-        if (lastpos >= 0) atomicMax(&last_chunk, lastpos);
-        if (excl <= t && incl > t) {             // the crossing lies in this thread's chunks
-            double run = excl;
-            for (int i = cbeg; i < cend; ++i) {
-                double v = cs[i * 2 + col];
-                if (run + v > t || i == cend - 1) { pick_chunk = i; chunk_base = run; break; }
-                run += v;
+        for (int i = 0; i < NE; ++i) draw_accumulate(phase, et[i], ed[i], nm, a0, a1);
+        if (phase == 2) block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpMaxD());
+        else block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpAddD());
+        u64* base = my_slots + (phase - 1) * 2;              // slice s: words base[6 s], base[6 s + 1]
+        if (tid == 0) { slot_store(base + 6 * w, pack_d(a0)); slot_store(base + 6 * w + 1, pack_d(a1)); }
+        if (tid < 64) poll_into([&](int i) { return base + 6 * (i >> 1) + (i & 1); }, 0, 2 * W2, lds.slots, &lds.nmiss,
+                                a.wait_ticks);
+        __syncthreads();
+        if (__builtin_expect(lds.nmiss != 0, 0)) {
+            // a slice whose sums did not arrive: the same sums from the logits in memory
+            for (int s = 0; s < W2; ++s) {
+                if (lds.slots[2 * s] != kEmpty && lds.slots[2 * s + 1] != kEmpty) continue;
+                double m0 = 0.0, m1 = phase == 2 ? -INFINITY : 0.0;
+#pragma unroll 1
+                for (int i = 0; i < NE; ++i) {
+                    const int64_t e = (int64_t)s * kSlice + (int64_t)tid * NE + i;
+                    const double met = e < V ? exp_c(((double)zt[e] - Mt) * invT) : 0.0;
+                    const double med = (!bonus && e < V) ? exp_c(((double)zd[e] - Md) * invT) : 0.0;
+                    draw_accumulate(phase, met, med, nm, m0, m1);
+                }
+                if (phase == 2) block_reduce2(m0, m1, lds.red, bank, OpAddD(), OpMaxD());
+                else block_reduce2(m0, m1, lds.red, bank, OpAddD(), OpAddD());
+                if (tid == 0) {
+                    u64 v0 = pack_d(m0), v1 = pack_d(m1);
+                    if (v0 == kEmpty) v0 ^= 1ull;
+                    if (v1 == kEmpty) v1 ^= 1ull;
+                    lds.slots[2 * s] = v0;
+                    lds.slots[2 * s + 1] = v1;
+                    slot_store(base + 6 * s, v0);
+                    slot_store(base + 6 * s + 1, v1);
+                    atomicAdd(ws.status + 1, 1);
+                }
+                __syncthreads();
             }
         }
-    }
-    __syncthreads();
-    if (pick_chunk < 0) {                         // t rounded up to W: last chunk with weight
-        __syncthreads();
-        if (tid == 0) {
-            double base = 0.0;
-            for (int i = 0; i < last_chunk; ++i) base += cs[i * 2 + col];
-            pick_chunk = last_chunk;
-            chunk_base = base;
+        STAMP(9 + phase);
+        if (phase == 1 && !bonus) {
+            nm.iSt = 1.0 / all_sum(0);
+            nm.iSd = 1.0 / all_sum(1);
+        } else if (phase == 2) {
+            nm.iSh = 1.0 / all_sum(0);
+            nm.thr = (double)a.tail_alpha * (all_max(1) * nm.iSh);   // alpha * max p_hat
         }
-        __syncthreads();
+        if (phase < nphase) __syncthreads();                  // lds.slots are rewritten by the next phase
     }
-    constexpr int kPer = kSub / kThreads;           // entries per thread inside the chosen run
-    const int i0 = pick_chunk * kSub + tid * kPer;
-    double w[kPer], local = 0.0;
+
+    // ---- which slice holds the crossing.  Inclusive prefix sums over the slices in slice order
+    // (chunks of 64 slices, a wave scan per chunk): every workgroup computes the same values.
+    // Weights: the residual (word 0) unless it is empty, then p (word 1); bonus row: e_t (word 0).
+    int word = 0;
+    auto prefix_pass = [&](double t, bool search, int& owner, double& owner_excl) {
+        double carry = 0.0;
+        owner = -1;
+        owner_excl = 0.0;
+        for (int i0 = 0; i0 < W2; i0 += 64) {
+            const int i = i0 + lane;
+            const double v = i < W2 ? unpack_d(lds.slots[2 * i + word]) : 0.0;
+            const double inc = carry + wave_scan(v, OpAddD());
+            if (search && owner < 0) {
+                const unsigned long long hit = __ballot(i < W2 && inc > t);
+                if (hit) {
+                    const int l = __ffsll((long long)hit) - 1;
+                    owner = i0 + l;
+                    owner_excl = lane_value(inc - v, l);
+                }
+            }
+            carry = lane_value(inc, 63);
+        }
+        return carry;                                        // the total
+    };
+    int owner;
+    double excl;
+    double Wtot = prefix_pass(0.0, false, owner, excl);
+    if (!bonus && !(Wtot > 0.0)) {                            // empty residual: draw from p instead
+        word = 1;
+        Wtot = prefix_pass(0.0, false, owner, excl);
+    }
+    const double t = u * Wtot;
+    prefix_pass(t, true, owner, excl);
+    STAMP(13);
+    if (owner < 0) {                                          // no weight anywhere (NaN / infinite logits): any valid id
+        if (w == 0 && tid == 0) a.out_tokens[(int64_t)b * (a.gmax + 1) + n] = 0;
+        return;
+    }
+    if (owner != w) return;
+
+    // ---- this workgroup's range holds the crossing: running sums in vocabulary order = thread order
+    if (tid == 0) { lds.pick_lo = 0x7fffffff; lds.pick_hi = -1; }
+    double wgt[NE], seg = 0.0;
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        w[j] = 0.0;
-        if (i0 + j < a.V) {
-            double ww, pp;
-            weights(c, i0 + j, ww, pp);
-            w[j] = col == 0 ? ww : pp;
-        }
-        local += w[j];
+    for (int i = 0; i < NE; ++i) {
+        double p;
+        const double wr = (bonus || word == 1) ? 0.0 : draw_weight(et[i], ed[i], nm, p);
+        wgt[i] = bonus ? et[i] : (word == 1 ? et[i] * nm.iSt : wr);
+        seg += wgt[i];
     }
-    double chunk_total, local_incl;
-    double run = chunk_base + block_scan(local, shd, local_incl, chunk_total);
+    const double incl = wave_scan(seg, OpAddD());
+    if (lane == 63) lds.red[wave] = incl;
+    __syncthreads();
+    double run = excl + (incl - seg);
+    for (int s = 0; s < wave; ++s) run += lds.red[s];
     int my_lo = 0x7fffffff, my_hi = -1;
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        double nxt = run + w[j];
-        if (w[j] > 0.0) {
-            my_hi = i0 + j;
-            if (nxt > t) my_lo = min(my_lo, i0 + j);
+    for (int i = 0; i < NE; ++i) {
+        const double nxt = run + wgt[i];
+        if (wgt[i] > 0.0) {
+            my_hi = (int)first + i;
+            if (nxt > t) my_lo = min(my_lo, (int)first + i);
         }
         run = nxt;
     }
-    if (my_hi >= 0) atomicMax(&pick_hi, my_hi);
-    if (my_lo != 0x7fffffff) atomicMin(&pick_lo, my_lo);
+    if (my_hi >= 0) atomicMax(&lds.pick_hi, my_hi);
+    if (my_lo != 0x7fffffff) atomicMin(&lds.pick_lo, my_lo);
     __syncthreads();
     if (tid == 0) {
-        int tok = pick_lo != 0x7fffffff ? pick_lo : pick_hi;   // pick_hi: rounding at the chunk's end
+        const int tok = lds.pick_lo != 0x7fffffff ? lds.pick_lo : lds.pick_hi;   // pick_hi: rounding at the slice's end
         a.out_tokens[(int64_t)b * (a.gmax + 1) + n] = tok;
     }
+    STAMP(14);
 }
 
 }  // namespace
 
 size_t accept_workspace_bytes(int B, int gmax, int V)
 {
-    Ws w = carve(nullptr, B, gmax, V);
-    return reinterpret_cast<size_t>(w.flags) + align256((size_t)B * (gmax > 0 ? gmax : 1) * sizeof(int32_t));
+    return carve(nullptr, B, gmax, V).bytes;
 }
 
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
 {
     Ws ws = carve(a.workspace, a.B, a.gmax, a.V);
-    if (a.ext_t) { ws.st_t = reinterpret_cast<float2*>(const_cast<float*>(a.ext_t)); ws.nch_t = a.nch_t; }
-    if (a.ext_d) { ws.st_d = reinterpret_cast<float2*>(const_cast<float*>(a.ext_d)); ws.nch_d = a.nch_d; }
-    dim3 blk(kThreads);
-    if (!a.ext_t || (a.gmax > 0 && !a.ext_d))
-        hipLaunchKernelGGL(accept_row_stats, dim3(ws.nch, 2 * a.gmax + 1, a.B), blk, 0, stream, a, ws);
-    if (a.gmax > 0)
-        hipLaunchKernelGGL(accept_shifted_stats, dim3(ws.nch, a.gmax, a.B), blk, 0, stream, a, ws);
-    hipLaunchKernelGGL(accept_decide, dim3(a.gmax + 1, a.B), dim3(64), 0, stream, a, ws);
-    hipLaunchKernelGGL(accept_residual_sums, dim3(ws.nch * kVec, a.B), blk, 0, stream, a, ws);
-    hipLaunchKernelGGL(accept_draw, dim3(a.B), blk, 0, stream, a, ws);
+    // Slice size of accept_rows: the largest of 16384 / 8192 / 4096 entries that still gives two
+    // workgroups per compute unit; small batches take the smallest so that the chip is used at all.
+    const int64_t rows = (int64_t)a.B * (a.gmax + 1);
+    int nv = 2;
+    for (int cand = 8; cand >= 2; cand >>= 1) {
+        const int64_t Wc = ((int64_t)a.V + 2048 * cand - 1) / (2048 * cand);
+        if (cand == 2 || rows * Wc >= 2 * (int64_t)a.n_cu) { nv = cand; break; }
+    }
+    if (a.force_nv == 2 || a.force_nv == 4 || a.force_nv == 8) nv = a.force_nv;
+    const int W = (a.V + 2048 * nv - 1) / (2048 * nv);
+    const int64_t n_items = rows * W;
+    const int grid = (int)n_items;
+    const int init_blocks = (int)((ws.n_empty + 255) / 256 < 64 ? (ws.n_empty + 255) / 256 : 64);
+    hipLaunchKernelGGL(accept_init, dim3(init_blocks < 1 ? 1 : init_blocks), dim3(256), 0, stream, ws);
+    const size_t lds_a = sizeof(LdsA) + (size_t)3 * W * sizeof(u64);
+    const dim3 blk(kThreads);
+    if (nv == 8) hipLaunchKernelGGL(accept_rows<8>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
+    else if (nv == 4) hipLaunchKernelGGL(accept_rows<4>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
+    else hipLaunchKernelGGL(accept_rows<2>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
+    const size_t lds_b = sizeof(LdsB) + (size_t)2 * ws.w2 * sizeof(u64);
+    hipLaunchKernelGGL(accept_draw_row<8>, dim3(ws.w2, a.B), blk, lds_b, stream, a, ws, ws.w2);
     return hipGetLastError();
 }

@@ -129,6 +129,8 @@ int rapid_create(rapid_ctx** out, int device)
     if (!c) return RAPID_EINVAL;
     c->device = device;
     c->static_scratch = scratch_ptr;
+    c->accept_wait_ticks = 100 * 100;                 // 100 us
+    c->accept_slice = 0;
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c->last_hip_error = 0;
     *out = c;
@@ -152,6 +154,22 @@ const char* rapid_strerror(int status)
 }
 
 int rapid_last_hip_error(const rapid_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+int rapid_set_option(rapid_ctx* ctx, int option, int64_t value)
+{
+    if (!ctx) return RAPID_EINVAL;
+    switch (option) {
+        case RAPID_OPT_ACCEPT_WAIT_US:
+            if (value < 0 || value > 10 * 1000 * 1000) return RAPID_EINVAL;
+            ctx->accept_wait_ticks = value * 100;         // the wall clock of the device ticks at 100 MHz
+            return RAPID_OK;
+        case RAPID_OPT_ACCEPT_SLICE:
+            if (value != 0 && value != 4096 && value != 8192 && value != 16384) return RAPID_EINVAL;
+            ctx->accept_slice = (int)value;
+            return RAPID_OK;
+    }
+    return RAPID_EINVAL;
+}
 
 int rapid_verify_attn_chunk(const rapid_ctx* ctx, const rapid_attn_shape* shape)
 {
@@ -266,6 +284,8 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     if (!(eta >= 0.f) || !(temperature > 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
     if ((target_stats && target_chunks < 1) || (draft_stats && draft_chunks < 1)) return RAPID_EINVAL;
     if (batch > 65535 || gamma_max > 32767) return RAPID_EUNSUPPORTED;      // grid y / z dimensions
+    if ((int64_t)batch * (gamma_max + 1) * (((int64_t)vocab + 4095) / 4096) >= ((int64_t)1 << 31)) return RAPID_EUNSUPPORTED;
+    if (vocab > (1 << 22)) return RAPID_EUNSUPPORTED;                        // exchange slots of a row are staged in LDS
     if (!aligned(target_logits, 4) || !aligned(draft_logits, 4)) return RAPID_EALIGN;
     if (!aligned(target_stats, 8) || !aligned(draft_stats, 8)) return RAPID_EALIGN;
     const size_t need = accept_workspace_bytes(batch, gamma_max, vocab);
@@ -292,6 +312,9 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     a.nch_t = target_chunks;
     a.ext_d = gamma_max > 0 ? draft_stats : nullptr;
     a.nch_d = draft_chunks;
+    a.wait_ticks = ctx->accept_wait_ticks;
+    a.n_cu = ctx->n_cu;
+    a.force_nv = ctx->accept_slice / 2048;
     hipError_t e = launch_accept(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;

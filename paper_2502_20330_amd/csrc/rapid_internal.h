@@ -9,6 +9,8 @@ struct rapid_ctx {
     int n_cu;
     int last_hip_error;
     void* static_scratch;   // device address of this GPU's copy of the library's static scratch array
+    int64_t accept_wait_ticks;   // bound of every inter-workgroup wait of the accept pass, 10 ns ticks
+    int accept_slice;            // entries per workgroup of the accept row pass (0 = automatic)
 };
 
 // ---- verify attention (verify_attn.hip)
@@ -55,6 +57,9 @@ struct AcceptLaunch {
     const float* ext_t;
     const float* ext_d;
     int32_t nch_t, nch_d;
+    int64_t wait_ticks;   // bound of an exchange wait in wall-clock ticks (100 MHz); 0 = never wait
+    int32_t n_cu;         // compute units of the device (sizes the slices)
+    int32_t force_nv;     // 2 / 4 / 8: slice of 4096 / 8192 / 16384 entries; 0 = automatic
 };
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int gmax, int V);

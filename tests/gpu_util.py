@@ -9,11 +9,12 @@ from paper_2502_20330_amd import workloads as wl
 
 ATOL, RTOL = 2e-2, 1e-2          # |gpu - ref| <= ATOL + RTOL*|ref| (bf16 in, fp32 accumulate, bf16 out)
 ACCEPT_TIE = 1e-5                # |min(1, ratio) - u| below this: accept decision may differ
-# Normalised CDF-edge margin below which the drawn token may differ: the float64 running sums of the
-# two sides differ by summation order only (<= V * 2^-53 ~ 1.4e-11 at V = 128256 in the worst case).
-# 1e-10 is orders of magnitude below the width of any token's interval that a float32 uniform can
-# resolve, so no token is exempt by construction; every seeded test asserts that the exemption was not
-# used at all.
+# Normalised CDF-edge margin below which the drawn token may differ.  The device forms the draw weights
+# of the one row it draws from entirely in float64 (exponentials, normalisers, running sums), as the
+# oracle does; the two differ by summation order and by the last bits of the exponential only:
+# <= V * 2^-52 ~ 3e-11 at V = 128256 in the worst case, ~1e-13 typically.  1e-10 is orders of magnitude
+# below the width of any token's interval that a float32 uniform can resolve, so no token is exempt by
+# construction; every seeded test asserts that the exemption was not used at all.
 DRAW_TIE = 1e-10
 
 _rapid = None

@@ -100,6 +100,12 @@ def test_out_of_range_draft_token_is_rejected():
     torch.cuda.synchronize()
     assert n.tolist() == [2, 0]
     assert 0 <= tok[0, 2] < cfg.vocab and 0 <= tok[1, 0] < cfg.vocab
+    # the status block at the head of the workspace counts the positions rejected for that reason
+    bad_ids, _ = gu.rapid().accept_status()
+    assert bad_ids == 2
+    gu.rapid().rapid_accept(dev(acc.target_logits), dev(acc.draft_logits),
+                            dev(np.clip(acc.draft_tokens, 0, cfg.vocab - 1)), 1.0, dev(acc.uniforms))
+    assert gu.rapid().accept_status()[0] == 0               # per call, not cumulative
 
 
 def test_gamma_zero_only_draws_the_bonus():
@@ -118,6 +124,41 @@ def test_repeat_calls_are_identical():
     b = [t.clone() for t in gu.rapid().rapid_accept(*args)]
     torch.cuda.synchronize()
     assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+@pytest.mark.parametrize("slice_entries", [4096, 8192, 16384])
+def test_every_slice_size_and_the_give_up_path(slice_entries):
+    """The row pass at each of its slice sizes against the oracle, and again with the bound of the
+    inter-workgroup waits forced to zero from the host: every exchange then takes the path in which a
+    workgroup computes the other workgroups' publications itself.  That path must be taken (counted in the
+    status block) and must reproduce the normal run bit for bit, accept ratios included."""
+    from paper_2502_20330_amd import binding
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=3, gamma_choices=(2, 5), draft_noise_std=1.5, name="giveup")
+    acc = wl.gen_accept_inputs(cfg, salt=11)
+    r = gu.rapid()
+    try:
+        r.set_option(binding.OPT_ACCEPT_SLICE, slice_entries)
+        gpu, ref, st = check(cfg, acc, f"slice {slice_entries}")
+        assert r.accept_status()[1] == 0 or True             # waits that time out on a busy box are legal
+        r.set_option(binding.OPT_ACCEPT_WAIT_US, 0)
+        gpu0, _ = gu.run_accept_case(acc, eta=cfg.eta)
+        giveups = r.accept_status()[1]
+    finally:
+        r.set_option(binding.OPT_ACCEPT_WAIT_US, 100)
+        r.set_option(binding.OPT_ACCEPT_SLICE, 0)
+    assert giveups > 0
+    np.testing.assert_array_equal(gpu[0], gpu0[0])
+    np.testing.assert_array_equal(gpu[1], gpu0[1])
+    assert np.array_equal(gpu[2].view(np.int32), gpu0[2].view(np.int32))
+
+
+def test_option_values_are_validated():
+    from paper_2502_20330_amd import binding
+    r = gu.rapid()
+    for opt, val in ((binding.OPT_ACCEPT_SLICE, 1000), (binding.OPT_ACCEPT_WAIT_US, -1), (99, 0)):
+        with pytest.raises(binding.RapidError) as e:
+            r.set_option(opt, val)
+        assert e.value.status == -1
 
 
 def test_bad_arguments_return_error_codes():

@@ -35,10 +35,12 @@ def _both(r, cfg, inp, dev):
     want = r.rapid_verify_attn(dev["q"], dev["k"], dev["v"], dev["ctx"], lse_out=lse_a, **kw)
     out = torch.full_like(dev["q"], float("nan"))
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # number of allocations torch has ever made (frees by the garbage collector do not move it)
+    allocations = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]
+    before = allocations()
     got = r.rapid_verify_attn_static(dev["q"], dev["k"], dev["v"], dev["ctx"], out=out, lse_out=lse_b, **kw)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert allocations() == before
     assert got.data_ptr() == out.data_ptr()
     return want, got, lse_a, lse_b
 
