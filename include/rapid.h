@@ -45,7 +45,7 @@ typedef enum rapid_status {
     RAPID_OK = 0,
     RAPID_EINVAL = -1,        /* NULL pointer, non-positive size, gamma/ctx out of range, eta < 0, T <= 0 */
     RAPID_EALIGN = -2,        /* q/k/v/out not 16-byte aligned, or a stride not a multiple of 8 elements  */
-    RAPID_EUNSUPPORTED = -3,  /* head_dim not 64/128, (gamma+1)*group > 80, page size not a power of two >= 16 */
+    RAPID_EUNSUPPORTED = -3,  /* head_dim not 64/128, (gamma+1)*group > 96, page size not a power of two >= 16 */
     RAPID_EWORKSPACE = -4,    /* workspace NULL, misaligned or smaller than the *_workspace_bytes() answer */
     RAPID_EHIP = -5,          /* a HIP runtime call failed */
     RAPID_ETOOLARGE = -6      /* rapid_verify_attn_static: the shape needs more than RAPID_STATIC_SCRATCH_BYTES */

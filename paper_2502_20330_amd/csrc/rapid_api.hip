@@ -11,6 +11,22 @@ static __device__ __align__(256) unsigned char scratch[RAPID_STATIC_SCRATCH_BYTE
 
 namespace {
 
+#ifndef RAPID_WIDE_FROM
+#define RAPID_WIDE_FROM 5
+#endif
+constexpr int kWideFromBlocks = RAPID_WIDE_FROM;    // row blocks from which the two-team attention kernel is used
+
+// Row blocks of 16 packed query rows that the partials of a shape are laid out in.  Five and six
+// blocks run on the two-team kernel, which works in pairs of blocks.
+int attn_row_blocks(const rapid_attn_shape* s, int* wide)
+{
+    const int G = s->n_q_heads / s->n_kv_heads;
+    const int rb = (s->q_max * G + 15) / 16;
+    const bool w = rb >= kWideFromBlocks;
+    if (wide) *wide = w ? 1 : 0;
+    return w ? (rb + 1) / 2 * 2 : rb;
+}
+
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 int hip_fail(rapid_ctx* ctx, hipError_t e)
@@ -30,7 +46,7 @@ int check_attn_shape(const rapid_attn_shape* s)
     if (s->head_dim != 64 && s->head_dim != 128) return RAPID_EUNSUPPORTED;
     if (s->batch > 65535) return RAPID_EUNSUPPORTED;                       // grid z dimension
     const int G = s->n_q_heads / s->n_kv_heads;
-    if ((int64_t)s->q_max * G > 80) return RAPID_EUNSUPPORTED;
+    if ((int64_t)s->q_max * G > 96) return RAPID_EUNSUPPORTED;
     if (s->page_size != 0) {
         if (s->page_size < 16 || (s->page_size & (s->page_size - 1))) return RAPID_EUNSUPPORTED;
         if (s->max_pages < 1 || (int64_t)s->max_pages * s->page_size < s->max_ctx) return RAPID_EINVAL;
@@ -183,8 +199,7 @@ size_t rapid_verify_attn_workspace_bytes(const rapid_ctx* ctx, const rapid_attn_
     if (check_attn_shape(shape) != RAPID_OK) return 0;
     const int chunk = plan_chunk(ctx, shape);
     const int nsplit = (shape->max_ctx + chunk - 1) / chunk;
-    const int G = shape->n_q_heads / shape->n_kv_heads;
-    const int RB = (shape->q_max * G + 15) / 16;
+    const int RB = attn_row_blocks(shape, nullptr);
     return attn_workspace_bytes(shape->batch, shape->n_kv_heads, nsplit, RB, shape->head_dim);
 }
 
@@ -222,7 +237,7 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
     a.max_ctx = shape->max_ctx;
     a.chunk = plan_chunk(ctx, shape);
     a.nsplit = (shape->max_ctx + a.chunk - 1) / a.chunk;
-    a.RB = (a.Qmax * a.G + 15) / 16;
+    a.RB = attn_row_blocks(shape, &a.wide);
     a.bstride = shape->kv_batch_stride;
     a.tstride = shape->kv_token_stride;
     a.hstride = shape->kv_head_stride;

@@ -511,6 +511,235 @@ __global__ void __launch_bounds__(kWaves * 64) verify_attn_split(AttnLaunch a)
     }
 }
 
+// ---------------------------------------------------------------- wide row counts: two row teams
+// Above 64 packed rows (five or six row blocks) one wave per SIMD is nearly compute bound: the MFMA
+// work and the softmax of a tile leave no slack to hide LDS and wait latency.  The wide kernel runs
+// eight waves: wave (team, p) = (wave / 4, wave % 4).  The two waves of pair p share the K/V ring of
+// token quarter p and each takes RBT of the 2*RBT row blocks, so every K/V byte is still fetched once
+// per workgroup and each SIMD holds two waves that fill each other's stalls.  Each wave of a pair
+// issues half of the load instructions of every tile and waits on its own counter; two workgroup
+// barriers per tile make the halves visible to the partner and tell it when a slot may be refilled:
+//     wait own K(it) | barrier A | issue V(it+1) | scores, softmax | wait own V(it) | barrier B |
+//     issue K(it+2) | PV
+// Barrier A: K(it) is complete, and everybody has finished PV(it-1), so V slot (it+1)&1 is free.
+// Barrier B: V(it) is complete, and everybody has finished the scores of it, so K slot it&1 is free.
+template <int D, bool PAGED, bool IS_V>
+__device__ __forceinline__ void dma_half_tile(const RowAddr& ra, uint32_t slot, int t0, int last_tok, int lane, int half)
+{
+    using G = Geo<D>;
+    const char* base = IS_V ? ra.vbase : ra.kbase;
+    const int r_local = lane / G::CPR, cpos = lane % G::CPR;
+#pragma unroll
+    for (int h = 0; h < G::NLD / 2; ++h) {
+        const int e = half * (G::NLD / 2) + h;
+        const int row = e * G::RPI + r_local;
+        const int c = cpos ^ (IS_V ? v_swz<D>(row) : k_swz<D>(row));
+        const int tok = min(t0 + row, last_tok);
+        if (PAGED) {
+            const int tok0 = min(t0 + e * G::RPI, last_tok);
+            const int64_t pg = ra.pages[tok0 >> ra.page_shift];
+            dma16(base + pg * ra.page_bytes, (uint32_t)(tok & ra.page_mask) * ra.tok_bytes + (uint32_t)c * 16u,
+                  slot + e * 1024);
+        } else {
+            dma16(base, (uint32_t)tok * ra.tok_bytes + (uint32_t)c * 16u, slot + e * 1024);
+        }
+    }
+}
+
+template <int D, int RBT>
+constexpr int attn_wide_lds_bytes()
+{
+    constexpr int tiles = kWaves * Geo<D>::WAVE_LDS + 2 * RBT * 16 * Geo<D>::ROWB;          // four rings + the Q block
+    constexpr int merge = (2 * 2 * RBT * 16 * (D + 4) + 2 * kWaves * RBT * 16 * 2) * 4;   // two teams' exchange buffers
+    return tiles > merge ? tiles : merge;
+}
+
+template <int D, int RBT, bool PAGED>
+__global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLaunch a)
+{
+    using G = Geo<D>;
+    constexpr int RPT = RBT * 16;          // rows of one team
+    constexpr int RP = 2 * RPT;            // rows of the workgroup (= a.RB * 16)
+    constexpr int kWait = G::NLD;          // own loads issued after the tile a wait is for (two half tiles)
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int split = blockIdx.y, b = blockIdx.z;
+    const int hkv = a.rot ? (int)((blockIdx.x + split) % a.Hkv) : (int)blockIdx.x;
+    const int L = min(a.ctx_lens[b], a.max_ctx);
+    const int c0 = split_begin(a, split, hkv);
+    if (c0 >= L) return;
+    const int c1 = min(split_end(a, split, hkv), L);
+    const int Q = seq_queries(a, b);
+    const int R = Q * a.G;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = wave >> 2, pr = wave & 3;          // row team, token quarter
+    const int ln = lane & 15, lg = lane >> 4;
+
+    const int ntile = (c1 - c0 + kTile - 1) / kTile;
+    const int ntq = (ntile + kWaves - 1) / kWaves;                              // tiles per quarter (uniform)
+    const int last_tok = min(c1, c0 + (pr + 1) * ntq * kTile) - 1;
+    auto tile_t0 = [&](int it) { return c0 + (pr * ntq + it) * kTile; };
+    const RowAddr addr = make_row_addr<PAGED>(a, b, hkv);
+    char* kring = smem + pr * G::WAVE_LDS;
+    char* vring = kring + 2 * G::SLOT;
+    const uint32_t kring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + pr * G::WAVE_LDS;
+    const uint32_t vring_lds = kring_lds + 2 * G::SLOT;
+
+    // Q block: RP rows, HBM -> LDS once per workgroup, the eight waves sharing the loads; issued
+    // before the first tiles so that it is complete when only tile loads are outstanding.
+    char* qlds = smem + kWaves * G::WAVE_LDS;
+    {
+        const uint32_t q_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + kWaves * G::WAVE_LDS;
+        constexpr int QI = RP / G::RPI;
+        const int last_row = a.Qmax * a.G - 1;
+        for (int e = wave; e < QI; e += 2 * kWaves) {
+            const int row = e * G::RPI + lane / G::CPR;
+            const int rr = min(row, last_row);
+            const int qi = rr / a.G, qg = rr % a.G;
+            const int c = (lane % G::CPR) ^ k_swz<D>(row);
+            const uint32_t off = (uint32_t)(((((int64_t)b * a.Qmax + qi) * a.Hq + hkv * a.G + qg) * D) * 2) + c * 16;
+            dma16_keep(reinterpret_cast<const char*>(a.q), off, q_lds + e * 1024);
+        }
+    }
+    // Pipeline start: K(0), V(0), K(1) (V(1) follows barrier A of the first iteration).  Every wave runs
+    // all ntq iterations, also over tiles past the end of the split (their loads are clamped, their
+    // keys masked), so that all eight waves meet at every barrier.
+    dma_half_tile<D, PAGED, false>(addr, kring_lds, tile_t0(0), last_tok, lane, team);
+    dma_half_tile<D, PAGED, true>(addr, vring_lds, tile_t0(0), last_tok, lane, team);
+    dma_half_tile<D, PAGED, false>(addr, kring_lds + G::SLOT, tile_t0(1), last_tok, lane, team);
+    wait_loads<3 * (G::NLD / 2)>();                      // everything older than the three half tiles: Q
+    __syncthreads();
+
+    bf16x8 qf[RBT][G::KS];
+    int lim[RBT];
+#pragma unroll
+    for (int rb = 0; rb < RBT; ++rb) {
+        const int row = team * RPT + rb * 16 + ln;
+        const bool real = row < R;
+        const int qi = real ? row / a.G : 0;
+        lim[rb] = min(real ? L - Q + qi : L - 1, c1 - 1);
+#pragma unroll
+        for (int ks = 0; ks < G::KS; ++ks) {
+            const int c = (ks * 4 + lg) ^ k_swz<D>(row);
+            u32x4 raw = *reinterpret_cast<const u32x4*>(qlds + row * G::ROWB + c * 16);
+            if (!real) raw = u32x4{0, 0, 0, 0};
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    WaveState<D, RBT> st;
+#pragma unroll
+    for (int rb = 0; rb < RBT; ++rb) {
+        st.m[rb] = -INFINITY;
+        st.l[rb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < G::DB; ++db) st.acc[db][rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float c = a.scale_log2e;
+    const int first_masked_t0 = min(L - Q, c1) - (kTile - 1);
+    // (tiles of this quarter past the end of the split start at t0 >= c1: every key of theirs is masked)
+
+    for (int it = 0; it < ntq; ++it) {
+        char* kt = kring + (it & 1) * G::SLOT;
+        char* vt = vring + (it & 1) * G::SLOT;
+        const int t0 = tile_t0(it);
+        floatx4 s[2][RBT];
+        bf16x8 pb[RBT];
+
+        wait_loads<kWait>();                         // own half of K(it) has landed
+        __syncthreads();                             // barrier A
+        dma_half_tile<D, PAGED, true>(addr, vring_lds + ((it + 1) & 1) * G::SLOT, tile_t0(it + 1), last_tok, lane, team);
+        score_tile<D, RBT>(s, qf, kt, lane);
+        softmax_tile<D, RBT>(st, s, pb, t0, t0 >= first_masked_t0, lim, c, lane);
+
+        wait_loads<kWait>();                         // own half of V(it) has landed
+        lds_reads_done();
+        __syncthreads();                             // barrier B
+        dma_half_tile<D, PAGED, false>(addr, kring_lds + (it & 1) * G::SLOT, tile_t0(it + 2), last_tok, lane, team);
+        pv_tile<D, RBT>(st, pb, vt, lane);
+        lds_reads_done();
+    }
+    wait_loads<0>();
+
+#pragma unroll
+    for (int rb = 0; rb < RBT; ++rb) {
+        st.l[rb] += __shfl_xor(st.l[rb], 16);
+        st.l[rb] += __shfl_xor(st.l[rb], 32);
+    }
+
+    // ---- combine the four waves of each team (fixed order) and write the split's partial
+    __syncthreads();                                  // all rings are dead from here on
+    constexpr int OROW = D + 4;
+    float* obuf = reinterpret_cast<float*>(smem) + team * 2 * RPT * OROW;     // this team's [2][RPT][OROW]
+    float* mlbuf = reinterpret_cast<float*>(smem) + 2 * 2 * RPT * OROW;       // [8 waves][RPT][2]
+    if (lg == 0) {
+#pragma unroll
+        for (int rb = 0; rb < RBT; ++rb) {
+            mlbuf[(wave * RPT + rb * 16 + ln) * 2 + 0] = st.m[rb];
+            mlbuf[(wave * RPT + rb * 16 + ln) * 2 + 1] = st.l[rb];
+        }
+    }
+    float* mine = obuf + (pr & 1) * RPT * OROW;
+    if (pr >= 2) {
+#pragma unroll
+        for (int db = 0; db < G::DB; ++db)
+#pragma unroll
+            for (int rb = 0; rb < RBT; ++rb)
+                *reinterpret_cast<floatx4*>(mine + (rb * 16 + ln) * OROW + db * 16 + lg * 4) = st.acc[db][rb];
+    }
+    __syncthreads();
+    float m_all[RBT], l_all[RBT];
+#pragma unroll
+    for (int rb = 0; rb < RBT; ++rb) {
+        const int row = rb * 16 + ln;
+        float mw[kWaves];
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            mw[w] = mlbuf[((team * kWaves + w) * RPT + row) * 2];
+            mm = fmaxf(mm, mw[w]);
+        }
+        const float m_use = (mm == -INFINITY) ? 0.f : mm;
+        float ll = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) ll += mlbuf[((team * kWaves + w) * RPT + row) * 2 + 1] * fast_exp2(mw[w] - m_use);
+        m_all[rb] = mm;
+        l_all[rb] = ll;
+        if (pr < 2) {
+            const float f_own = fast_exp2(mw[pr] - m_use), f_par = fast_exp2(mw[pr + 2] - m_use);
+#pragma unroll
+            for (int db = 0; db < G::DB; ++db) {
+                float* cell = mine + row * OROW + db * 16 + lg * 4;
+                floatx4 other = *reinterpret_cast<const floatx4*>(cell);
+                *reinterpret_cast<floatx4*>(cell) = st.acc[db][rb] * f_own + other * f_par;
+            }
+        }
+    }
+    __syncthreads();
+    const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.nsplit + split) * RP;
+    floatx4* po = reinterpret_cast<floatx4*>(a.part_o + pbase * D);
+    const float* oall = reinterpret_cast<const float*>(smem);
+    for (int f = tid; f < R * (D / 4); f += 2 * kWaves * 64) {
+        const int row = f / (D / 4), d4 = f % (D / 4);
+        const int tm = row / RPT, lr = row % RPT;
+        const float* ob = oall + tm * 2 * RPT * OROW;
+        const floatx4 x = *reinterpret_cast<const floatx4*>(ob + lr * OROW + d4 * 4);
+        const floatx4 y = *reinterpret_cast<const floatx4*>(ob + (RPT + lr) * OROW + d4 * 4);
+        po[f] = x + y;
+    }
+    if (pr == 0 && lg == 0) {
+#pragma unroll
+        for (int rb = 0; rb < RBT; ++rb) {
+            const int row = team * RPT + rb * 16 + ln;
+            if (row < R) {
+                a.part_ml[(pbase + row) * 2 + 0] = m_all[rb];
+                a.part_ml[(pbase + row) * 2 + 1] = l_all[rb];
+            }
+        }
+    }
+}
+
 // Merge the splits of one query row: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // One workgroup of D threads per (sequence, kv head, packed row), splits taken 32 at a
 // time.  The kernel is latency bound, so every thread issues the loads of its column
@@ -605,6 +834,22 @@ hipError_t launch_split(const AttnLaunch& a, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int D, int RBT, bool PAGED>
+hipError_t launch_split_wide(const AttnLaunch& a, hipStream_t stream)
+{
+    constexpr int lds = attn_wide_lds_bytes<D, RBT>();
+    auto fn = verify_attn_split_wide<D, RBT, PAGED>;
+    dim3 grid(a.Hkv, a.nsplit, a.B), block(2 * kWaves * 64);
+    hipLaunchKernelGGL(fn, grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+template <int D, int RBT, bool PAGED>
+hipError_t configure_split_wide()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(verify_attn_split_wide<D, RBT, PAGED>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, attn_wide_lds_bytes<D, RBT>());
+}
+
 // The split kernels use more dynamic LDS than the default limit allows; raise it once
 // per device, ahead of any launch (and so outside any stream capture).
 template <int D, int RB, bool PAGED>
@@ -621,12 +866,19 @@ hipError_t configure_rb()
     if ((e = configure_split<D, 2, PAGED>()) != hipSuccess) return e;
     if ((e = configure_split<D, 3, PAGED>()) != hipSuccess) return e;
     if ((e = configure_split<D, 4, PAGED>()) != hipSuccess) return e;
-    return configure_split<D, 5, PAGED>();
+    if ((e = configure_split<D, 5, PAGED>()) != hipSuccess) return e;
+    if ((e = configure_split_wide<D, 2, PAGED>()) != hipSuccess) return e;
+    return configure_split_wide<D, 3, PAGED>();
 }
 
 template <int D, bool PAGED>
 hipError_t dispatch_rb(const AttnLaunch& a, hipStream_t stream)
 {
+    if (a.wide) {                                    // a.RB = 2 RBT row blocks
+        if (a.RB == 4) return launch_split_wide<D, 2, PAGED>(a, stream);
+        if (a.RB == 6) return launch_split_wide<D, 3, PAGED>(a, stream);
+        return hipErrorInvalidValue;
+    }
     switch (a.RB) {
         case 1: return launch_split<D, 1, PAGED>(a, stream);
         case 2: return launch_split<D, 2, PAGED>(a, stream);

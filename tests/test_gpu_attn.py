@@ -85,6 +85,31 @@ def test_group_sizes_and_gammas(hq, hkv, gam):
     check(cfg, chunk_tokens=512)
 
 
+@pytest.mark.parametrize("L", [12, 40, 129, 300, 1023, 1024, 1025, 2500, 4133])
+@pytest.mark.parametrize("gam,group", [(10, 8), (8, 8), (11, 8), (9, 7)])
+def test_wide_row_counts_two_row_teams(L, gam, group):
+    """65..96 packed rows run on the eight-wave kernel (two row teams per KV ring).  gamma = 10 with group
+    size 8 is the paper's setting for its 70B / 72B targets (88 rows).  Lengths from fewer tokens than one
+    tile per token quarter up to several splits, so that whole quarters of a split are empty."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], n_q_heads=2 * group, n_kv_heads=2, gamma_choices=(gam,),
+                    ctx=(L, L), name=f"wide_g{group}_gamma{gam}_L{L}")
+    check(cfg, chunk_tokens=1024 if L > 1024 else 0)
+
+
+def test_wide_row_counts_layouts_and_ragged_batches():
+    base = dict(n_q_heads=16, n_kv_heads=2, name="wide_layouts")
+    # ragged batch, per-sequence gamma (some sequences have far fewer rows than the kernel is sized for)
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=3, ctx=(700, 5000), gamma_choices=(10, 3), **base)
+    inp = wl.gen_attn_inputs(cfg, layer=3)
+    check(cfg, inp, chunk_tokens=640)
+    check(cfg, inp, chunk_tokens=640, head_major=True, what="wide head-major")
+    # paged cache, head_dim 64, peaked softmax (unscaled keys)
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=2, ctx=(900, 3000), gamma_choices=(10,), paged=True, k_scale=1.0, **base)
+    check(cfg, chunk_tokens=512, what="wide paged peaked")
+    cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=24, n_kv_heads=3, ctx=(3000, 3000), gamma_choices=(10,), name="wide_d64")
+    check(cfg, chunk_tokens=1024)
+
+
 def test_head_dim_64_multi_split():
     cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=16, n_kv_heads=4, ctx=(5000, 5000), name="d64")
     check(cfg, chunk_tokens=1024)
@@ -173,9 +198,9 @@ def test_bad_arguments_return_error_codes():
     with pytest.raises(binding.RapidError) as e:       # head_dim 96
         r.rapid_verify_attn(q[..., :96].contiguous(), k[..., :96].contiguous(), k[..., :96].contiguous(), ctx)
     assert e.value.status == -3
-    q80 = torch.zeros(1, 11, 8, 128, dtype=torch.bfloat16, device="cuda")    # 11*8 = 88 rows > 80
+    q104 = torch.zeros(1, 13, 8, 128, dtype=torch.bfloat16, device="cuda")   # 13*8 = 104 packed rows > 96
     with pytest.raises(binding.RapidError) as e:
-        r.rapid_verify_attn(q80, k, k, ctx)
+        r.rapid_verify_attn(q104, k, k, ctx)
     assert e.value.status == -3
     with pytest.raises(binding.RapidError) as e:       # scale <= 0
         r.rapid_verify_attn(q, k, k, ctx, softmax_scale=0.0)
@@ -241,6 +266,14 @@ def test_llama70b_128k_layer_full_size():
     """Config 5 shape (64 query heads, group 8 -> 72 packed rows), one layer."""
     cfg = wl.CONFIGS["llama70b_128k_step"]
     check(cfg, wl.gen_attn_inputs(cfg, layer=0), what=f"{cfg.name}[layer 0]")
+
+
+@pytest.mark.parametrize("head_major", [False, True])
+def test_paper_setting_gamma_10_group_8_at_128k_full_size(head_major):
+    """gamma = 10 (Sec. 3, implementation details) on the 70B / 72B head shape (64 query / 8 kv heads):
+    88 packed rows, 128K tokens, one layer, both cache orders, in the launch configuration of the benchmark."""
+    cfg = wl.scaled(wl.CONFIGS["llama70b_128k_step"], gamma_choices=(10,), name="llama70b_gamma10_128k")
+    check(cfg, wl.gen_attn_inputs(cfg, layer=1), what=f"{cfg.name}[head_major={head_major}]", head_major=head_major)
 
 
 def test_hbm_read_probe_runs_and_checks_arguments():

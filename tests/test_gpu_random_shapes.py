@@ -27,7 +27,7 @@ def _attn_cases(n=36):
         d = int(rng.choice([64, 128]))
         hkv = int(rng.choice([1, 2, 3, 4, 8]))
         gmax = int(rng.integers(0, 11))
-        g_hi = max(1, 80 // (gmax + 1))
+        g_hi = max(1, 96 // (gmax + 1))
         group = int(rng.integers(1, min(8, g_hi) + 1))
         batch = int(rng.choice([1, 1, 2, 3, 5]))
         lo = int(rng.integers(gmax + 1, 400))
