@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--with-lm-head", action="store_true",
                     help="also run the target's output head (hidden x vocab bf16 weights) inside every step and feed "
                          "its logits and row statistics to the accept pass (batch 1 workloads)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the short extra measurements of the other 128K configurations (the `also` object)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -62,6 +64,100 @@ def profile_traffic(kernel_key: str):
             if m:
                 return float(m.group(1))
     return None
+
+
+def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
+    """A short measurement of another workload (`n_layers` of its attention layers over rotating caches of at
+    least 1 GiB, and its accept pass): per-layer attention time, effective KV GB/s, fraction of peak."""
+    import numpy as np
+    import torch
+
+    from paper_2502_20330_amd import workloads as wl
+    dev = r.device
+    lib = r.lib
+    seqs = wl.gen_sequences(cfg)
+    B, Q, Hq, Hkv, d = cfg.batch, cfg.q_max, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    ctx_lens = torch.from_numpy(seqs.ctx_lens).to(dev)
+    gammas = torch.from_numpy(seqs.gammas).to(dev)
+    page_table = torch.from_numpy(seqs.page_table).to(dev) if cfg.paged else None
+    kv_shape = (seqs.n_pages, cfg.page_size, Hkv, d) if cfg.paged else (B, seqs.max_ctx, Hkv, d)
+
+    def kv_randn(g):
+        if head_major:
+            return torch.randn((kv_shape[0], Hkv, kv_shape[1], d), dtype=torch.bfloat16, device=dev,
+                               generator=g).permute(0, 2, 1, 3)
+        return torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g)
+
+    tokens_alloc = (seqs.n_pages * cfg.page_size) if cfg.paged else B * seqs.max_ctx
+    nbuf = max(n_layers, -(-(1 << 30) // (tokens_alloc * cfg.kv_bytes_per_token())))
+    nbuf = -(-nbuf // n_layers) * n_layers
+    ks, vs, qs = [], [], []
+    for layer in range(nbuf):
+        g = torch.Generator(device=dev)
+        g.manual_seed(1000 * wl.SEED_QKV + layer)
+        k = kv_randn(g)
+        if cfg.k_scale != 1.0:
+            k.mul_(cfg.k_scale)
+        ks.append(k)
+        vs.append(kv_randn(g))
+        qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
+    out = torch.empty_like(qs[0])
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.SEED_LOGITS)
+    gmax, V = cfg.gamma_max, cfg.vocab
+    zt = torch.randn((B, gmax + 1, V), device=dev, generator=g) * cfg.logit_std
+    zd = (zt[:, :gmax] + torch.randn((B, gmax, V), device=dev, generator=g) * cfg.draft_noise_std).contiguous()
+    gumbel = -torch.log(-torch.log(torch.rand((B, gmax, V), device=dev, generator=g).clamp_min(1e-20)))
+    draft_tokens = torch.argmax(zd / cfg.temperature + gumbel, dim=-1).to(torch.int32)
+    del gumbel
+    uniforms = torch.rand((B, gmax + 1), device=dev, generator=g)
+    n_acc = torch.empty(B, dtype=torch.int32, device=dev)
+    out_tok = torch.empty((B, gmax + 1), dtype=torch.int32, device=dev)
+    tokens = int(seqs.ctx_lens.astype(np.int64).sum())
+    shape = r.attn_shape(qs[0], ks[0], seqs.max_ctx, page_table=page_table, softmax_scale=cfg.softmax_scale,
+                         ctx_sum_hint=tokens)
+    ws = torch.empty(max(lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape)),
+                         lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V), 256), dtype=torch.uint8, device=dev)
+    stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    P = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
+    attn_args = [(r._ctx, ctypes.byref(shape), P(qs[l]), P(ks[l]), P(vs[l]), P(ctx_lens), P(gammas), P(page_table),
+                  P(out), None, P(ws), ws.numel(), stream) for l in range(nbuf)]
+    acc_args = (r._ctx, B, gmax, V, P(zt), P(zd), P(draft_tokens), P(gammas), float(cfg.eta), float(cfg.temperature),
+                float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), None, P(ws), ws.numel(), stream)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(f"librapid status {rc}: {lib.rapid_strerror(rc).decode()}")
+
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    attn_ms = acc_ms = 0.0
+    for it in range(warmup + steps):
+        first = (it * n_layers) % nbuf
+        e[0].record()
+        for a in attn_args[first:first + n_layers]:
+            check(lib.rapid_verify_attn(*a))
+        e[1].record()
+        check(lib.rapid_accept(*acc_args))
+        e[2].record()
+        torch.cuda.synchronize()
+        if it >= warmup:
+            attn_ms += e[0].elapsed_time(e[1])
+            acc_ms += e[1].elapsed_time(e[2])
+    per_layer_us = attn_ms / (steps * n_layers) * 1e3
+    kv_bytes_layer = tokens * cfg.kv_bytes_per_token()
+    gbps = kv_bytes_layer / (per_layer_us * 1e-6) / 1e9
+    logit_bytes = int(sum((2 * int(gb) + 1) * V * 4 for gb in seqs.gammas))
+    acc_us = acc_ms / steps * 1e3
+    del ks, vs, qs, attn_args
+    torch.cuda.empty_cache()
+    return {"layers_timed": n_layers, "layers_of_the_workload": cfg.layers, "steps": steps, "batch": B,
+            "ctx_tokens": tokens, "packed_rows": Q * (Hq // Hkv), "kv_bytes_per_layer": kv_bytes_layer,
+            "rotating_cache_bytes": nbuf * tokens_alloc * cfg.kv_bytes_per_token(),
+            "attention_per_layer_us": round(per_layer_us, 2), "attention_gbps": round(gbps, 1),
+            "attention_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "accept_us": round(acc_us, 2), "accept_logit_bytes": logit_bytes,
+            "accept_gbps": round(logit_bytes / (acc_us * 1e-6) / 1e9, 1),
+            "accept_frac_of_peak": round(logit_bytes / (acc_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
 
 
 def main():
@@ -285,6 +381,16 @@ def main():
                                       "algorithmic_bytes_per_launch": w_bytes,
                                       "traffic": profile_traffic("rapid_lm_head") if cfg.name == "llama8b_128k_step" else None}
 
+    # ---------------------------------------------------------------- the other 128K configurations, briefly
+    if cfg.name == "llama8b_128k_step" and not args.no_also and not head:
+        del ks, vs, qs, attn_args
+        torch.cuda.empty_cache()
+        result["also"] = {name: also_workload(r, wl.CONFIGS[name], n_layers, head_major)
+                          for name, n_layers in (("ragged_paged", 1), ("llama70b_128k_step", 8))}
+        also_mode = True
+    else:
+        also_mode = False
+
     # ---------------------------------------------------------------- oracle on the host cores (baseline only)
     if not args.no_cpu_baseline:
         import oracle
@@ -293,6 +399,19 @@ def main():
         bs, ts, hs, ps = wl.kv_strides(cfg, seqs)
         lay = oracle.KVLayout(bs, ts, hs, cfg.page_size if cfg.paged else 0, ps,
                               seqs.page_table.shape[1] if cfg.paged else 0)
+        if also_mode:                   # the caches were released for the extra workloads: same seeds again
+            ks, vs, qs = [], [], []
+            for layer in range(nl):
+                g = torch.Generator(device=dev)
+                g.manual_seed(1000 * wl.SEED_QKV + layer)
+                k = kv_randn(g)
+                if cfg.k_scale != 1.0:
+                    k.mul_(cfg.k_scale)
+                ks.append(k)
+                vs.append(kv_randn(g))
+                qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
+            attn_args = [(r._ctx, ctypes.byref(shape), P(qs[l]), P(ks[l]), P(vs[l]), P(ctx_lens), P(gammas), P(page_table),
+                          P(outs[l & 1]), None, P(ws), ws.numel(), stream) for l in range(nl)]
         host = [(to_bits(qs[l]), to_bits(ks[l]), to_bits(vs[l])) for l in range(nl)]
         acc_host = (zt.cpu().numpy(), zd.cpu().numpy(), draft_tokens.cpu().numpy(), uniforms.cpu().numpy())
         worst = 0.0
