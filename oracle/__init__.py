@@ -49,6 +49,7 @@ def _load():
         lib.oracle_retrieve.restype = ctypes.c_int
         lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_chunk_stats.restype = ctypes.c_int
+        lib.oracle_kv_commit_pages.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -232,6 +233,26 @@ def kv_commit(ctx_lens, n_accepted, *, gamma=None, gammas=None):
     if rc != 0:
         raise ValueError(f"oracle_kv_commit: invalid argument (rc={rc})")
     return out
+
+
+def kv_commit_pages(ctx_lens, n_accepted, page_table, page_size: int, cap: int, *, gamma=None, gammas=None):
+    """Paged commit: returns (new ctx_lens, released int32 [B, cap] page ids then -1, n_released int32 [B])."""
+    lib = _load()
+    out = np.array(ctx_lens, dtype=np.int32, copy=True)
+    n_accepted = np.ascontiguousarray(n_accepted, dtype=np.int32)
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    gammas = None if gammas is None else np.ascontiguousarray(gammas, dtype=np.int32)
+    B = len(out)
+    rel = np.empty((B, cap), dtype=np.int32)
+    cnt = np.empty(B, dtype=np.int32)
+    rc = lib.oracle_kv_commit_pages(ctypes.c_int(B), _ptr(gammas, ctypes.c_int32),
+                                    ctypes.c_int(0 if gamma is None else gamma), _ptr(n_accepted, ctypes.c_int32),
+                                    _ptr(page_table, ctypes.c_int32), ctypes.c_int(page_table.shape[1]),
+                                    ctypes.c_int(page_size), _ptr(out, ctypes.c_int32), _ptr(rel, ctypes.c_int32),
+                                    ctypes.c_int(cap), _ptr(cnt, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_commit_pages: invalid argument (rc={rc})")
+    return out, rel, cnt
 
 
 def retrieve(emb, query, top_k: int, threshold: float):

@@ -427,6 +427,41 @@ int oracle_kv_commit(int B, const int32_t* gammas, int gamma, const int32_t* n_a
 }
 
 
+/* Commit for a paged cache, with the allocator's view of the roll-back:  */
+/* after the length update above, the page-table slots j of sequence b    */
+/* with ceil(L_new / page) <= j < ceil(L_old / page) hold nothing the     */
+/* sequence keeps (only rejected verification positions lived there);     */
+/* their page ids are listed in ascending slot order, the row padded      */
+/* with -1.  released: int32 [B][cap], n_released: int32 [B].             */
+int oracle_kv_commit_pages(int B, const int32_t* gammas, int gamma, const int32_t* n_accepted,
+                           const int32_t* page_table, int max_pages, int page_size,
+                           int32_t* ctx_lens, int32_t* released, int cap, int32_t* n_released)
+{
+    if (B < 1 || !n_accepted || !ctx_lens || !page_table || !released || !n_released || page_size < 1 || cap < 0)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        const int g = gammas ? gammas[b] : gamma;
+        if (n_accepted[b] < 0 || n_accepted[b] > g || ctx_lens[b] < g + 1) return -2;
+        const int l_old = ctx_lens[b];
+        const int l_new = l_old - (g + 1) + (1 + n_accepted[b]);
+        int cnt = 0;
+        for (int j = 0; j < max_pages; ++j) {
+            /* slot j covers tokens j*page .. j*page + page - 1 */
+            const int used_before = j * page_size < l_old;
+            const int used_after = j * page_size < l_new;
+            if (used_before && !used_after) {
+                if (cnt >= cap) return -3;
+                released[(int64_t)b * cap + cnt++] = page_table[(int64_t)b * max_pages + j];
+            }
+        }
+        n_released[b] = cnt;
+        for (int j = cnt; j < cap; ++j) released[(int64_t)b * cap + j] = -1;
+        ctx_lens[b] = l_new;
+    }
+    return 0;
+}
+
+
 /* ------------------------------------------------------------------ */
 /* Retrieval: which chunks of the long context the drafter gets.        */
 /*   emb   float [n][dim] chunk embeddings, query float [dim]            */

@@ -88,3 +88,44 @@ def test_commit_per_sequence_gammas_and_bad_input():
     assert out.tolist() == [100, 46, 9]
     with pytest.raises(ValueError):
         oracle.kv_commit(np.array([100]), np.array([5]), gamma=4)
+
+
+def test_paged_commit_releases_exactly_the_pages_nothing_kept_lives_in():
+    """Pin of the page bookkeeping by explicit sets: simulate every token's page-table slot, collect the slots
+    that hold a token before the commit and none after it; the oracle must list the page ids of exactly those
+    slots, in slot order, and never a slot that still holds a kept token."""
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        page = int(rng.choice([1, 2, 4, 16, 32]))
+        gamma = int(rng.integers(0, 11))
+        n = int(rng.integers(0, gamma + 1))
+        l_old = int(rng.integers(gamma + 1, 200))
+        max_pages = -(-200 // page) + 2
+        table = rng.permutation(1000)[:max_pages].astype(np.int32)[None]
+        cap = (gamma + 1 + page - 2) // page + 1
+        new, rel, cnt = oracle.kv_commit_pages(np.array([l_old]), np.array([n]), table, page, cap, gamma=gamma)
+        l_new = l_old - (gamma + 1) + (1 + n)
+        assert new[0] == l_new
+        slots_before = {t // page for t in range(l_old)}
+        slots_after = {t // page for t in range(l_new)}
+        want = sorted(slots_before - slots_after)
+        assert rel[0, :cnt[0]].tolist() == [int(table[0, j]) for j in want]
+        assert np.all(rel[0, cnt[0]:] == -1)
+        assert cnt[0] <= cap
+
+
+def test_paged_commit_hand_cases():
+    table = np.arange(100, 120, dtype=np.int32)[None]          # slot j -> page 100 + j
+    # 16-token pages, 40 tokens incl. 9 verification positions (tokens 31..39), 2 drafts accepted -> 34 tokens:
+    # slots 0..2 were in use (tokens 0..39), slots 0..2 are still needed (tokens 32, 33 live in slot 2): nothing freed
+    new, rel, cnt = oracle.kv_commit_pages(np.array([40]), np.array([2]), table, 16, 2, gamma=8)
+    assert new.tolist() == [34] and cnt.tolist() == [0] and rel.tolist() == [[-1, -1]]
+    # nothing accepted -> 32 tokens = exactly two pages: slot 2 is freed
+    new, rel, cnt = oracle.kv_commit_pages(np.array([40]), np.array([0]), table, 16, 2, gamma=8)
+    assert new.tolist() == [32] and cnt.tolist() == [1] and rel.tolist() == [[102, -1]]
+    # 4-token pages: tokens 31..39 sit in slots 7, 8, 9; keep 32 -> slots 8 and 9 go
+    new, rel, cnt = oracle.kv_commit_pages(np.array([40]), np.array([0]), table, 4, 4, gamma=8)
+    assert cnt.tolist() == [2] and rel[0, :2].tolist() == [108, 109]
+    # everything accepted: nothing to free
+    new, rel, cnt = oracle.kv_commit_pages(np.array([40]), np.array([8]), table, 4, 4, gamma=8)
+    assert new.tolist() == [40] and cnt.tolist() == [0]
