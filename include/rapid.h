@@ -103,7 +103,9 @@ typedef struct rapid_attn_shape {
     int32_t page_size;        /* 0 = contiguous cache, else a power of two >= 16               */
     int32_t max_pages;        /* row length of page_table                                      */
     int32_t chunk_tokens;     /* tokens per KV split; 0 = let the library choose               */
-    int32_t reserved;         /* set to 0                                                      */
+    int32_t n_pages;          /* pages in the pool, 0 = unknown: page_table entries (device data) are  */
+                              /* clamped to [0, n_pages) before use; with 0 only negative entries are  */
+                              /* clamped and larger ones are the caller's responsibility                */
     int64_t ctx_sum_hint;     /* sum of ctx_lens[b] if the host knows it (a scheduler usually  */
                               /* does), else 0: only used to size the KV splits of ragged      */
                               /* batches; results never depend on it                           */
@@ -283,13 +285,30 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
  * token and the n_accepted[b] accepted drafts (the newly drawn token has no key/value yet):
  *     ctx_lens[b] <- ctx_lens[b] - (gamma_b + 1) + (1 + n_accepted[b])
  * in place, on the device (n_accepted is rapid_accept's output; values outside
- * [0, gamma_b] are clamped).  gammas == NULL: `gamma` for every sequence.
+ * [0, gamma_b] are clamped).  gammas == NULL: `gamma` for every sequence; otherwise gammas[b]
+ * (device data) is clamped to >= 0 and, when gamma > 0, to <= gamma.
+ *
+ * rapid_kv_commit_pages: the same length update for a paged cache, and the bookkeeping a page
+ * allocator needs after the roll-back: the pages of sequence b that held verification positions
+ * only and lie wholly past the committed length can be handed back.  With L_old = ctx_lens[b] on
+ * entry and L_new the committed length, these are the page-table slots j with
+ *     ceil(L_new / page_size) <= j < ceil(L_old / page_size);
+ * their page ids are written in ascending slot order to released_pages[b], the rest of the row is
+ * -1, and n_released[b] is their number.  The page table itself is not modified (the caller
+ * decides when to reuse the pages).  gamma_b is clamped to [0, q_max - 1] and L_old to max_ctx.
+ *   shape           as for rapid_verify_attn (page_size > 0 required)
+ *   released_pages  int32 [B, release_cap]; release_cap >= (q_max + page_size - 2) / page_size + 1
+ *                   (RAPID_EINVAL if smaller)
+ *   n_released      int32 [B]
  */
 int rapid_kv_append(rapid_ctx* ctx, const rapid_attn_shape* shape, const void* k_new, const void* v_new,
                     const int32_t* ctx_lens, const int32_t* gammas, const int32_t* page_table,
                     void* k_cache, void* v_cache, void* stream);
 int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas, const int32_t* n_accepted,
                     int32_t* ctx_lens, void* stream);
+int rapid_kv_commit_pages(rapid_ctx* ctx, const rapid_attn_shape* shape, const int32_t* gammas,
+                          const int32_t* n_accepted, const int32_t* page_table, int32_t* ctx_lens,
+                          int32_t* released_pages, int release_cap, int32_t* n_released, void* stream);
 
 /*
  * Chunk selection of the RAG drafter (Sec. 2.2; "RAG Setup" in Sec. 3): the long context is

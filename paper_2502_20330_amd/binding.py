@@ -24,6 +24,7 @@ EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_er
            "rapid_verify_attn_static",
            "rapid_accept_workspace_bytes", "rapid_accept", "rapid_accept_prestats",
            "rapid_lm_head_chunk", "rapid_lm_head_stat_chunks", "rapid_lm_head", "rapid_kv_append", "rapid_kv_commit",
+           "rapid_kv_commit_pages",
            "rapid_retrieve", "rapid_hbm_read_probe"]
 
 
@@ -41,7 +42,7 @@ class AttnShape(ctypes.Structure):
                 ("kv_batch_stride", ctypes.c_int64), ("kv_token_stride", ctypes.c_int64),
                 ("kv_head_stride", ctypes.c_int64), ("kv_page_stride", ctypes.c_int64),
                 ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
-                ("chunk_tokens", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("chunk_tokens", ctypes.c_int32), ("n_pages", ctypes.c_int32),
                 ("ctx_sum_hint", ctypes.c_int64)]
 
 
@@ -100,6 +101,9 @@ def load_library() -> ctypes.CDLL:
     lib.rapid_kv_append.restype = ctypes.c_int
     lib.rapid_kv_commit.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, i32p, i32p, i32p, vp]
     lib.rapid_kv_commit.restype = ctypes.c_int
+    lib.rapid_kv_commit_pages.argtypes = [ctypes.c_void_p, ctypes.POINTER(AttnShape), i32p, i32p, i32p, i32p, i32p,
+                                          ctypes.c_int, i32p, vp]
+    lib.rapid_kv_commit_pages.restype = ctypes.c_int
     lib.rapid_retrieve.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, f32p, f32p, ctypes.c_int, ctypes.c_float,
                                    f32p, i32p, i32p, vp]
     lib.rapid_retrieve.restype = ctypes.c_int
@@ -187,7 +191,7 @@ class Rapid:
             s.kv_batch_stride = 0
             s.page_size, s.max_pages = k_cache.shape[1], page_table.shape[1]
         s.chunk_tokens = int(chunk_tokens)
-        s.reserved = 0
+        s.n_pages = 0 if page_table is None else int(k_cache.shape[0])
         s.ctx_sum_hint = int(ctx_sum_hint)
         return s
 
@@ -307,6 +311,25 @@ class Rapid:
                                       _dptr(ctx_lens), _stream_ptr(self.device))
         _check(self.lib, rc, self._ctx)
         return ctx_lens
+
+    def rapid_kv_commit_pages(self, ctx_lens, n_accepted, page_table, *, page_size: int, q_max: int, max_ctx: int,
+                              gamma: Optional[int] = None, gammas=None, n_pages: int = 0):
+        """The length update of :meth:`rapid_kv_commit` for a paged cache plus the page ids that can be handed
+        back to the allocator.  Returns (released int32 [B, cap] (page ids, then -1), n_released int32 [B])."""
+        B = ctx_lens.numel()
+        s = AttnShape()
+        s.batch, s.q_max, s.n_q_heads, s.n_kv_heads, s.head_dim = B, q_max, 1, 1, 128
+        s.max_ctx, s.gamma, s.softmax_scale = int(max_ctx), (q_max - 1 if gamma is None else int(gamma)), 1.0
+        s.kv_token_stride, s.kv_head_stride, s.kv_page_stride = 128, 128, 128 * page_size
+        s.page_size, s.max_pages, s.n_pages = int(page_size), page_table.shape[1], int(n_pages)
+        cap = (q_max + page_size - 2) // page_size + 1
+        rel = torch.empty((B, cap), dtype=torch.int32, device=self.device)
+        cnt = torch.empty(B, dtype=torch.int32, device=self.device)
+        rc = self.lib.rapid_kv_commit_pages(self._ctx, ctypes.byref(s), _dptr(gammas), _dptr(n_accepted),
+                                            _dptr(page_table), _dptr(ctx_lens), _dptr(rel), cap, _dptr(cnt),
+                                            _stream_ptr(self.device))
+        _check(self.lib, rc, self._ctx)
+        return rel, cnt
 
     # ------------------------------------------------------------------ retrieval
     def rapid_retrieve(self, chunk_emb, query_emb, top_k: int, threshold: float = 0.3):

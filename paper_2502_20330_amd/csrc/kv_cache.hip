@@ -25,7 +25,7 @@ __global__ void __launch_bounds__(256) kv_append_rows(KvAppendLaunch a)
     if (tok < 0) return;                                   // malformed length: nothing to write
     int64_t base;
     if (a.page_shift >= 0) {
-        const int64_t pg = a.page_table[(int64_t)b * a.max_pages + (tok >> a.page_shift)];
+        const int64_t pg = min(max(a.page_table[(int64_t)b * a.max_pages + (tok >> a.page_shift)], 0), a.page_hi);
         base = pg * a.pstride + (tok & a.page_mask) * a.tstride;
     } else {
         base = (int64_t)b * a.bstride + tok * a.tstride;
@@ -46,9 +46,33 @@ __global__ void __launch_bounds__(256) kv_commit_lengths(int B, int gamma, const
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    const int g = gammas ? gammas[b] : gamma;
+    int g = gamma;
+    if (gammas) {                                           // device data: kept inside the range the caller states
+        g = max(gammas[b], 0);
+        if (gamma > 0) g = min(g, gamma);
+    }
     const int n = min(max(n_accepted[b], 0), g);
     ctx_lens[b] = ctx_lens[b] - (g + 1) + (1 + n);
+}
+
+// One thread per sequence: the length update, and the page-table slots that lie wholly past the
+// committed length (at most a handful: the verification positions span few pages).
+__global__ void __launch_bounds__(256) kv_commit_pages(KvCommitPagesLaunch a)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.B) return;
+    const int g = min(max(a.gammas ? a.gammas[b] : a.gamma, 0), a.Qmax - 1);
+    const int n = min(max(a.n_accepted[b], 0), g);
+    const int l_old = min(max(a.ctx_lens[b], 0), a.max_ctx);
+    const int l_new = max(l_old - (g + 1) + (1 + n), 0);
+    const int ps = 1 << a.page_shift;
+    const int first = (l_new + ps - 1) >> a.page_shift, end = min((l_old + ps - 1) >> a.page_shift, a.max_pages);
+    int cnt = 0;
+    for (int j = first; j < end && cnt < a.cap; ++j)
+        a.released[(int64_t)b * a.cap + cnt++] = min(max(a.page_table[(int64_t)b * a.max_pages + j], 0), a.page_hi);
+    a.n_released[b] = cnt;
+    for (int j = cnt; j < a.cap; ++j) a.released[(int64_t)b * a.cap + j] = -1;
+    a.ctx_lens[b] = l_new;
 }
 
 }  // namespace
@@ -56,6 +80,12 @@ __global__ void __launch_bounds__(256) kv_commit_lengths(int B, int gamma, const
 hipError_t launch_kv_append(const KvAppendLaunch& a, hipStream_t stream)
 {
     hipLaunchKernelGGL(kv_append_rows, dim3(a.Qmax, a.B), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_commit_pages(const KvCommitPagesLaunch& a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(kv_commit_pages, dim3((a.B + 255) / 256), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -11,6 +11,25 @@ static __device__ __align__(256) unsigned char scratch[RAPID_STATIC_SCRATCH_BYTE
 
 namespace {
 
+// Makes the context's device current for the duration of a call and restores the caller's.
+struct DeviceScope {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceScope(int device)
+    {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != device) {
+            err = hipSetDevice(device);
+            switched = err == hipSuccess;
+        }
+    }
+    ~DeviceScope() { if (switched) (void)hipSetDevice(prev); }
+};
+
+// Largest page id a kernel may use: ids are device data and are clamped to [0, page_hi].
+int page_hi_of(const rapid_attn_shape* s) { return s->n_pages > 0 ? s->n_pages - 1 : 0x7fffffff; }
+
 #ifndef RAPID_WIDE_FROM
 #define RAPID_WIDE_FROM 5
 #endif
@@ -42,7 +61,7 @@ int check_attn_shape(const rapid_attn_shape* s)
     if (s->n_q_heads % s->n_kv_heads) return RAPID_EINVAL;
     if (s->gamma < 0 || s->gamma >= s->q_max || s->max_ctx < s->q_max) return RAPID_EINVAL;
     if (!(s->softmax_scale > 0.f)) return RAPID_EINVAL;
-    if (s->chunk_tokens < 0 || s->ctx_sum_hint < 0) return RAPID_EINVAL;
+    if (s->chunk_tokens < 0 || s->ctx_sum_hint < 0 || s->n_pages < 0) return RAPID_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return RAPID_EUNSUPPORTED;
     if (s->batch > 65535) return RAPID_EUNSUPPORTED;                       // grid z dimension
     const int G = s->n_q_heads / s->n_kv_heads;
@@ -251,6 +270,7 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
         a.page_shift = sh;
         a.page_mask = shape->page_size - 1;
     }
+    a.page_hi = page_hi_of(shape);
     a.scale_log2e = shape->softmax_scale * 1.4426950408889634f;
     plan_layout(ctx, a);
     const size_t rows = (size_t)a.B * a.Hkv * a.nsplit * a.RB * 16;
@@ -258,6 +278,8 @@ int rapid_verify_attn(rapid_ctx* ctx, const rapid_attn_shape* shape,
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + o_bytes);
 
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_verify_attn(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
@@ -330,6 +352,8 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     a.wait_ticks = ctx->accept_wait_ticks;
     a.n_cu = ctx->n_cu;
     a.force_nv = ctx->accept_slice / 2048;
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_accept(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
@@ -392,6 +416,8 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
     a.ldz = logits_row_stride;
     a.nb = lm_head_blocks(ctx, vocab);
     a.inv_T = (float)(1.0 / (double)temperature);
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_lm_head(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
@@ -434,6 +460,9 @@ int rapid_kv_append(rapid_ctx* ctx, const rapid_attn_shape* shape, const void* k
         a.page_shift = sh;
         a.page_mask = shape->page_size - 1;
     }
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
+    a.page_hi = page_hi_of(shape);
     hipError_t e = launch_kv_append(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
@@ -443,7 +472,42 @@ int rapid_kv_commit(rapid_ctx* ctx, int batch, int gamma, const int32_t* gammas,
                     int32_t* ctx_lens, void* stream)
 {
     if (!ctx || batch < 1 || gamma < 0 || !n_accepted || !ctx_lens) return RAPID_EINVAL;
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_kv_commit(batch, gamma, gammas, n_accepted, ctx_lens, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return RAPID_OK;
+}
+
+int rapid_kv_commit_pages(rapid_ctx* ctx, const rapid_attn_shape* shape, const int32_t* gammas,
+                          const int32_t* n_accepted, const int32_t* page_table, int32_t* ctx_lens,
+                          int32_t* released_pages, int release_cap, int32_t* n_released, void* stream)
+{
+    if (!ctx) return RAPID_EINVAL;
+    const int rc = check_attn_shape(shape);
+    if (rc != RAPID_OK) return rc;
+    if (shape->page_size == 0 || !n_accepted || !page_table || !ctx_lens || !released_pages || !n_released) return RAPID_EINVAL;
+    if (release_cap < (shape->q_max + shape->page_size - 2) / shape->page_size + 1) return RAPID_EINVAL;
+    KvCommitPagesLaunch a{};
+    a.gammas = gammas;
+    a.n_accepted = n_accepted;
+    a.page_table = page_table;
+    a.ctx_lens = ctx_lens;
+    a.released = released_pages;
+    a.n_released = n_released;
+    a.B = shape->batch;
+    a.Qmax = shape->q_max;
+    a.gamma = shape->gamma;
+    a.max_ctx = shape->max_ctx;
+    a.max_pages = shape->max_pages;
+    a.cap = release_cap;
+    a.page_hi = page_hi_of(shape);
+    int sh = 0;
+    while ((1 << sh) < shape->page_size) ++sh;
+    a.page_shift = sh;
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
+    hipError_t e = launch_kv_commit_pages(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
 }
@@ -465,6 +529,8 @@ int rapid_retrieve(rapid_ctx* ctx, int n_chunks, int dim, const float* chunk_emb
     a.dim = dim;
     a.top_k = top_k;
     a.threshold = threshold;
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_retrieve(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
@@ -475,6 +541,8 @@ int rapid_hbm_read_probe(rapid_ctx* ctx, const void* buf, size_t bytes, void* si
     if (!ctx || !buf) return RAPID_EINVAL;
     if (bytes < 16384 || bytes % 16384 || bytes >= ((size_t)1 << 46)) return RAPID_EINVAL;
     if (!aligned(buf, 16) || (sink && !aligned(sink, 4))) return RAPID_EALIGN;
+    DeviceScope dev(ctx->device);
+    if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
     hipError_t e = launch_hbm_read_probe(ctx, buf, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;

@@ -33,6 +33,7 @@ struct AttnLaunch {
     int32_t skew;       // tokens moved from the splits on odd dispatch slots to those on even ones
     int64_t bstride, tstride, hstride, pstride;   // elements
     int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
+    int32_t page_hi;    // largest page id the kernels will use (ids are clamped to [0, page_hi])
     float scale_log2e;
 };
 hipError_t launch_verify_attn(const AttnLaunch& a, hipStream_t stream);
@@ -96,7 +97,18 @@ struct KvAppendLaunch {
     int32_t max_ctx;
     int64_t bstride, tstride, hstride, pstride;   // elements
     int32_t page_shift, page_mask, max_pages;     // page_shift < 0: contiguous
+    int32_t page_hi;            // page ids are clamped to [0, page_hi]
 };
+struct KvCommitPagesLaunch {
+    const int32_t* gammas;
+    const int32_t* n_accepted;
+    const int32_t* page_table;
+    int32_t* ctx_lens;
+    int32_t* released;          // [B][cap]
+    int32_t* n_released;        // [B]
+    int32_t B, Qmax, gamma, max_ctx, page_shift, max_pages, cap, page_hi;
+};
+hipError_t launch_kv_commit_pages(const KvCommitPagesLaunch& a, hipStream_t stream);
 hipError_t launch_kv_append(const KvAppendLaunch& a, hipStream_t stream);
 hipError_t launch_kv_commit(int B, int gamma, const int32_t* gammas, const int32_t* n_accepted, int32_t* ctx_lens,
                             hipStream_t stream);

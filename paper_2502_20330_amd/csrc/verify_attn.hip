@@ -88,6 +88,7 @@ struct RowAddr {
     uint32_t tok_bytes;        // bytes between consecutive tokens
     int64_t page_bytes;        // bytes between pages
     int page_shift, page_mask;
+    int page_hi;               // page ids (device data) are clamped to [0, page_hi]
 };
 
 template <bool PAGED>
@@ -102,6 +103,7 @@ __device__ __forceinline__ RowAddr make_row_addr(const AttnLaunch& a, int b, int
     r.page_bytes = a.pstride * 2;
     r.page_shift = a.page_shift;
     r.page_mask = a.page_mask;
+    r.page_hi = a.page_hi;
     return r;
 }
 
@@ -146,7 +148,7 @@ __device__ __forceinline__ void dma_tile(const RowAddr& ra, uint32_t slot, int t
         if (PAGED) {
             // the RPI rows of one instruction lie in one page (pages hold >= 16 tokens)
             const int tok0 = min(t0 + e * G::RPI, last_tok);
-            const int64_t pg = ra.pages[tok0 >> ra.page_shift];
+            const int64_t pg = min(max(ra.pages[tok0 >> ra.page_shift], 0), ra.page_hi);
             dma16(base + pg * ra.page_bytes, (uint32_t)(tok & ra.page_mask) * ra.tok_bytes + (uint32_t)c * 16u,
                   slot + e * 1024);
         } else {
@@ -537,7 +539,7 @@ __device__ __forceinline__ void dma_half_tile(const RowAddr& ra, uint32_t slot, 
         const int tok = min(t0 + row, last_tok);
         if (PAGED) {
             const int tok0 = min(t0 + e * G::RPI, last_tok);
-            const int64_t pg = ra.pages[tok0 >> ra.page_shift];
+            const int64_t pg = min(max(ra.pages[tok0 >> ra.page_shift], 0), ra.page_hi);
             dma16(base + pg * ra.page_bytes, (uint32_t)(tok & ra.page_mask) * ra.tok_bytes + (uint32_t)c * 16u,
                   slot + e * 1024);
         } else {

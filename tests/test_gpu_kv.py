@@ -112,3 +112,43 @@ def test_whole_validation_round_on_device():
     if res["exempt_sequences"] == 0:
         assert np.array_equal(ctx.cpu().numpy(), oracle.kv_commit(s.ctx_lens, ref_acc.n_accepted, gammas=s.gammas))
     assert np.array_equal(ctx.cpu().numpy(), oracle.kv_commit(s.ctx_lens, n_acc.cpu().numpy(), gammas=s.gammas))
+
+
+def test_paged_commit_lists_released_pages():
+    """rapid_kv_commit_pages against the oracle, bit for bit: lengths, released page ids, counts; several page
+    sizes, per-sequence gammas, every accepted count."""
+    rng = np.random.default_rng(5)
+    for page in (16, 32, 128):
+        B, gmax = 37, 10
+        gam = rng.integers(0, gmax + 1, size=B).astype(np.int32)
+        n = np.array([rng.integers(0, g + 1) for g in gam], dtype=np.int32)
+        ctx = np.array([rng.integers(g + 1, 5000) for g in gam], dtype=np.int32)
+        max_pages = -(-5000 // page) + 1
+        table = np.stack([rng.permutation(4000)[:max_pages] for _ in range(B)]).astype(np.int32)
+        cap = (gmax + 1 + page - 2) // page + 1
+        want_len, want_rel, want_cnt = oracle.kv_commit_pages(ctx, n, table, page, cap, gammas=gam)
+        lens = torch.from_numpy(ctx.copy()).cuda()
+        rel, cnt = gu.rapid().rapid_kv_commit_pages(lens, torch.from_numpy(n).cuda(), torch.from_numpy(table).cuda(),
+                                                    page_size=page, q_max=gmax + 1, max_ctx=5000,
+                                                    gammas=torch.from_numpy(gam).cuda(), n_pages=4000)
+        torch.cuda.synchronize()
+        assert np.array_equal(lens.cpu().numpy(), want_len)
+        assert np.array_equal(cnt.cpu().numpy(), want_cnt)
+        assert np.array_equal(rel.cpu().numpy(), want_rel)
+        assert want_cnt.max() >= 1                      # the case is exercised
+
+
+def test_page_ids_outside_the_pool_are_clamped():
+    """Page-table entries are device data: with the pool size stated in the shape, entries outside [0, n_pages)
+    are clamped before they are used as addresses (the result then reads some valid page; it must not fault)."""
+    cfg = wl.scaled(wl.CONFIGS["ragged_paged"], name="bad_pages", batch=2, ctx=(300, 900))
+    inp = wl.gen_attn_inputs(cfg, layer=2)
+    s = inp.seqs
+    bad = s.page_table.copy()
+    bad[0, 3] = 1 << 30
+    bad[1, 0] = -5
+    q, k, v = gu.bf16_to_dev(inp.q), gu.bf16_to_dev(inp.k), gu.bf16_to_dev(inp.v)
+    out = gu.rapid().rapid_verify_attn(q, k, v, torch.from_numpy(s.ctx_lens).cuda(), gammas=torch.from_numpy(s.gammas).cuda(),
+                                       page_table=torch.from_numpy(bad).cuda(), max_ctx=s.max_ctx)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
