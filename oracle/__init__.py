@@ -50,6 +50,7 @@ def _load():
         lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_chunk_stats.restype = ctypes.c_int
         lib.oracle_kv_commit_pages.restype = ctypes.c_int
+        lib.oracle_accept_greedy.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -142,6 +143,32 @@ def accept(target_logits, draft_logits, draft_tokens, uniforms, *, eta, temperat
     if rc != 0:
         raise ValueError(f"oracle_accept: invalid argument (rc={rc})")
     return AcceptResult(n_acc, out_tok, ratio, amargin, dmargin)
+
+
+def accept_greedy(target_logits, draft_logits, draft_tokens, uniforms, *, gammas=None) -> AcceptResult:
+    """The T -> 0 limit of :func:`accept` (see ``oracle_accept_greedy``); draw_margin is 1 (no uniform is used)."""
+    lib = _load()
+    zt = np.ascontiguousarray(target_logits, dtype=np.float32)
+    zd = np.ascontiguousarray(draft_logits, dtype=np.float32)
+    B, g1, V = zt.shape
+    gmax = g1 - 1
+    assert zd.shape == (B, gmax, V)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gmax)
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    assert u.shape == (B, gmax + 1)
+    if gammas is not None:
+        gammas = np.ascontiguousarray(gammas, dtype=np.int32)
+    n_acc = np.empty((B,), dtype=np.int32)
+    out_tok = np.empty((B, gmax + 1), dtype=np.int32)
+    ratio = np.full((B, gmax), np.nan, dtype=np.float64)
+    amargin = np.full((B, gmax), np.inf, dtype=np.float64)
+    rc = lib.oracle_accept_greedy(ctypes.c_int(B), ctypes.c_int(gmax), ctypes.c_int64(V), _ptr(zt, ctypes.c_float),
+                                  _ptr(zd, ctypes.c_float), _ptr(tok, ctypes.c_int32), _ptr(gammas, ctypes.c_int32),
+                                  _ptr(u, ctypes.c_float), _ptr(n_acc, ctypes.c_int32), _ptr(out_tok, ctypes.c_int32),
+                                  _ptr(ratio, ctypes.c_double), _ptr(amargin, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_accept_greedy: invalid argument (rc={rc})")
+    return AcceptResult(n_acc, out_tok, ratio, amargin, np.ones((B,), dtype=np.float64))
 
 
 def distributions(z, zq, *, eta, temperature=1.0, tail_alpha=0.1):

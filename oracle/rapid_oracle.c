@@ -30,6 +30,8 @@
  *       How a uniform number is turned into a token (inverse CDF in index
  *       order) is an interface convention of this build, not the paper's.
  *
+ *   oracle_accept_greedy -- the T -> 0 limit of the same loop (see the function).
+ *
  *   oracle_lm_head      -- what "LogitsOf" (Alg. 1) means for a decoder
  *       language model: the logits of a position are its final hidden state
  *       times the output embedding, z[r][v] = sum_k h[r][k] * W[v][k] (no
@@ -329,6 +331,74 @@ int oracle_accept(int B, int gmax, int64_t V,
         }
         n_accepted[b] = n;
         free(z); free(zq); free(p); free(q); free(ph); free(w);
+    }
+    return 0;
+}
+
+
+/*
+ * The greedy limit T -> 0 of the validation loop (the paper runs T = 0.1 on one of its
+ * benchmarks, Appendix C; at T = 0 the softmaxes of Alg. 1 are no longer defined and the
+ * limit is taken instead).  With m = max_v z_v and m_q = max_v zq_v, as T -> 0:
+ *   p -> one-hot on argmax z, q -> one-hot on argmax zq, zh = z + eta T (q - p) -> z, so
+ *   ph -> p and the tail rule changes nothing;
+ *   ph(x')/q(x') = exp(((z_x' - m) - (zq_x' - m_q)) / T) * (bounded factor)
+ *        -> infinity if the target's gap z_x' - m is above the drafter's gap zq_x' - m_q,
+ *        -> 0 if it is below, -> 1 if the gaps are equal (both 0 when x' is the arg-max of both);
+ *   the residual max(p - ph, p - q, 0) -> p - q, positive only on argmax z (when the two
+ *   arg-maxima differ), and empty otherwise, where the rule falls back to p: either way the
+ *   token emitted on a rejection is argmax z of that row; the bonus token is argmax z of row g.
+ *   (This is the limit for a draft that is the drafter's own arg-max, which is what a drafter
+ *   emits at T -> 0.  For a rejected draft that is not, the literal limit of the residual also
+ *   depends on the runner-up gaps of both rows; such ids have probability 0 under q and the rule
+ *   here still emits argmax z.)
+ * Equal maxima: the lowest index counts as the arg-max (a convention; ties have probability 0
+ * for continuous logits).  The accept test stays the literal r <= min(1, ratio limit).
+ * eta and tail_alpha do not enter.  ratio: the limit (0, 1 or infinity); accept_margin as in
+ * oracle_accept.  No uniform drives the draw.
+ */
+int oracle_accept_greedy(int B, int gmax, int64_t V,
+                         const float* target_logits, const float* draft_logits,
+                         const int32_t* draft_tokens, const int32_t* gammas,
+                         const float* uniforms,
+                         int32_t* n_accepted, int32_t* out_tokens,
+                         double* ratio, double* accept_margin)
+{
+    if (B < 0 || gmax < 0 || V <= 0) return -1;
+    for (int b = 0; b < B; ++b) {
+        int g = gammas ? gammas[b] : gmax;
+        if (g < 0 || g > gmax) return -1;
+        for (int k = 0; k < g; ++k) {
+            int32_t x = draft_tokens[(int64_t)b * gmax + k];
+            if (x < 0 || x >= V) return -1;
+        }
+    }
+    for (int b = 0; b < B; ++b) {
+        const int g = gammas ? gammas[b] : gmax;
+        int32_t* toks = out_tokens + (int64_t)b * (gmax + 1);
+        for (int k = 0; k <= gmax; ++k) toks[k] = -1;
+        int n = g;
+        for (int k = 0; k < g; ++k) {
+            const float* z  = target_logits + ((int64_t)b * (gmax + 1) + k) * V;
+            const float* zq = draft_logits + ((int64_t)b * gmax + k) * V;
+            double m = -INFINITY, mq = -INFINITY;
+            for (int64_t v = 0; v < V; ++v) { if (z[v] > m) m = z[v]; if (zq[v] > mq) mq = zq[v]; }
+            const int32_t x = draft_tokens[(int64_t)b * gmax + k];
+            const double gap_t = (double)z[x] - m, gap_d = (double)zq[x] - mq;
+            const double rho = gap_t > gap_d ? INFINITY : (gap_t < gap_d ? 0.0 : 1.0);
+            const double r = uniforms[(int64_t)b * (gmax + 1) + k];
+            const double thr = rho < 1.0 ? rho : 1.0;
+            if (ratio) ratio[(int64_t)b * gmax + k] = rho;
+            if (accept_margin) accept_margin[(int64_t)b * gmax + k] = fabs(thr - r);
+            if (n == g && !(r <= thr)) n = k;
+        }
+        for (int k = 0; k < n; ++k) toks[k] = draft_tokens[(int64_t)b * gmax + k];
+        /* rejection at row n < g, or the bonus position n = g: the target's arg-max of that row */
+        const float* z = target_logits + ((int64_t)b * (gmax + 1) + n) * V;
+        int64_t best = 0;
+        for (int64_t v = 1; v < V; ++v) if (z[v] > z[best]) best = v;      /* strict: lowest index wins */
+        toks[n] = (int32_t)best;
+        n_accepted[b] = n;
     }
     return 0;
 }

@@ -471,3 +471,89 @@ def test_draw_margin_is_zero_when_the_target_rounds_up_to_the_total():
     r = oracle.accept(zt, zd, np.array([[0]], np.int32), np.array([[0.0, 1.0]], np.float32), eta=0.0, tail_alpha=0.0)
     assert r.n_accepted[0] == 1 and r.draw_margin[0] == 0.0
     assert r.out_tokens[0, 1] == 3                       # the last entry whose weight is positive
+
+
+# ---------------------------------------------------------------- the greedy limit T -> 0
+def test_greedy_limit_equals_small_temperature_runs():
+    """The T -> 0 rule is pinned against the general oracle at small temperatures.  The ratio of Alg. 1 behaves
+    like exp((target gap - drafter gap) / T), so wherever the two gaps differ by more than 0.5 (or are both 0)
+    T = 0.05 and 0.03 already sit in the limit: ratios are e^(+-10) and beyond, far from any uniform in
+    [0.01, 0.99].  (Much smaller T would underflow q(x') to 0 in float64, which the general oracle treats as
+    'accept'.)  Sequences with a closer call, or whose deciding row has a runner-up within 0.5 of the maximum,
+    are left out; the gaps are computed here from the logits.  Drafts are the drafter's arg-max for two thirds
+    of the sequences and arbitrary tokens for the rest; eta = 0, 5 and 50.  Prefix lengths are compared for
+    all of them; the emitted token only where the rejected draft was the drafter's arg-max (what a greedy
+    drafter proposes): for other ids the literal limit of the residual depends on the runner-up gaps and the
+    greedy rule emits the target's arg-max instead (a stated deviation for inputs of probability 0)."""
+    rng = np.random.default_rng(21)
+    B, g, V = 300, 5, 200
+    zt = rng.normal(0, 3, (B, g + 1, V)).astype(np.float32)
+    zd = (zt[:, :g] + rng.normal(0, 2.0, (B, g, V))).astype(np.float32)
+    tok = np.argmax(zd, -1).astype(np.int32)
+    tok[::3] = rng.integers(0, V, size=tok[::3].shape)
+    u = (rng.random((B, g + 1)) * 0.98 + 0.01).astype(np.float32)
+    lim = oracle.accept_greedy(zt, zd, tok, u)
+    z64, zd64 = zt.astype(np.float64), zd.astype(np.float64)
+    idx = tok[..., None].astype(np.int64)
+    gap_t = np.take_along_axis(z64[:, :g], idx, -1)[..., 0] - z64[:, :g].max(-1)
+    gap_d = np.take_along_axis(zd64, idx, -1)[..., 0] - zd64.max(-1)
+    diff = gap_t - gap_d
+    top2 = np.sort(z64, -1)[..., -1] - np.sort(z64, -1)[..., -2]                       # [B, g+1]
+    all_argmax = np.all(gap_d == 0, axis=1)                                            # the drafter's own arg-max everywhere
+    n = lim.n_accepted
+    stop_is_argmax = np.array([n[b] == g or gap_d[b, n[b]] == 0 for b in range(B)])
+    for T, eta in ((0.05, 0.0), (0.03, 0.0), (0.03, 5.0), (0.005, 50.0)):
+        # in the limit when the gap difference outweighs the mixing term (which moves scores by up to 2 eta) and
+        # any uniform: (2 eta + ln 100) T, with margin
+        need = max(0.5, 1.5 * (2 * eta + 4.6) * T)
+        clear = np.all((np.abs(diff) > need) | ((gap_t == 0) & (gap_d == 0)), axis=1) & (top2[np.arange(B), n] > need)
+        if T < 0.03:
+            clear &= all_argmax                      # q(x') of an arbitrary id underflows to 0 at this temperature
+        assert clear.sum() >= 40 and 0 < n[clear].mean() < g, (T, eta, clear.sum())
+        gen = oracle.accept(zt, zd, tok, u, eta=eta, temperature=T, tail_alpha=0.1)
+        np.testing.assert_array_equal(gen.n_accepted[clear], n[clear])
+        sel = clear & stop_is_argmax
+        assert sel.sum() >= 30
+        np.testing.assert_array_equal(gen.out_tokens[sel], lim.out_tokens[sel])
+    assert len(set(n[(np.arange(B) % 3 == 0) & np.all(np.abs(diff) > 0.5, axis=1)].tolist())) >= 2   # arbitrary ids: both outcomes
+
+
+def test_greedy_limit_hand_cases():
+    z = np.array([[[1.0, 5.0, 2.0], [0.0, 0.0, 9.0], [4.0, 4.0, 1.0]]], dtype=np.float32)     # arg-max 1, 2, 0 (tie -> lowest)
+    zq = np.array([[[0.0, 3.0, 1.0], [7.0, 1.0, 6.5]]], dtype=np.float32)                       # arg-max 1, 0
+    u = np.array([[0.5, 0.5, 0.123]], dtype=np.float32)
+    # drafts (1, 0): position 0 agrees with the target; position 1 is the drafter's arg-max but not the target's
+    r = oracle.accept_greedy(z, zq, np.array([[1, 0]], np.int32), u)
+    assert r.n_accepted.tolist() == [1] and r.out_tokens.tolist() == [[1, 2, -1]]
+    assert r.ratio[0].tolist() == [1.0, 0.0]
+    # drafts (1, 2): both are the target's arg-max -> all accepted, bonus = arg-max of row 2 with the tie broken low;
+    # token 2 at position 1 is not the drafter's arg-max: its gap (-0.5) is below the target's (0) -> ratio infinite
+    r = oracle.accept_greedy(z, zq, np.array([[1, 2]], np.int32), u)
+    assert r.n_accepted.tolist() == [2] and r.out_tokens.tolist() == [[1, 2, 0]]
+    assert r.ratio[0, 0] == 1.0 and np.isinf(r.ratio[0, 1])
+    # a token that is nobody's arg-max: target gap 1 - 5 = -4, drafter gap 0 - 3 = -3 -> rejected; 2: gaps -3, -2 -> rejected
+    r = oracle.accept_greedy(z, zq, np.array([[0, 2]], np.int32), u)
+    assert r.n_accepted.tolist() == [0] and r.out_tokens.tolist() == [[1, -1, -1]]
+    # equal gaps (-3 and -3): the limit of the ratio is 1 -> accepted
+    zq2 = zq.copy(); zq2[0, 0] = [0.0, 5.0, 2.0]
+    r = oracle.accept_greedy(z, zq2, np.array([[2, 2]], np.int32), u)
+    assert r.ratio[0, 0] == 1.0 and r.n_accepted.tolist() == [2]
+    # a uniform of exactly 0 passes even a ratio of 0 (the literal r <= min(1, ratio))
+    # (position 1 then holds the target's arg-max, so everything is accepted and the bonus row decides the last token)
+    r = oracle.accept_greedy(z, zq, np.array([[0, 2]], np.int32), np.array([[0.0, 0.5, 0.1]], np.float32))
+    assert r.n_accepted.tolist() == [2] and r.out_tokens.tolist() == [[0, 2, 0]]
+    r = oracle.accept_greedy(z, zq, np.array([[0, 0]], np.int32), np.array([[0.0, 0.5, 0.1]], np.float32))
+    assert r.n_accepted.tolist() == [1] and r.out_tokens.tolist() == [[0, 2, -1]]
+
+
+def test_greedy_limit_identical_logits_and_gammas():
+    rng = np.random.default_rng(4)
+    zt = rng.normal(0, 3, (6, 5, 50)).astype(np.float32)
+    tok = np.argmax(zt[:, :4], -1).astype(np.int32)
+    gam = np.array([4, 2, 0, 4, 1, 3], dtype=np.int32)
+    r = oracle.accept_greedy(zt, zt[:, :4].copy(), tok, rng.random((6, 5)).astype(np.float32), gammas=gam)
+    assert r.n_accepted.tolist() == gam.tolist()
+    for b in range(6):
+        g = int(gam[b])
+        assert r.out_tokens[b, :g].tolist() == tok[b, :g].tolist()
+        assert r.out_tokens[b, g] == int(np.argmax(zt[b, g])) and np.all(r.out_tokens[b, g + 1:] == -1)
