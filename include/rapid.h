@@ -43,7 +43,7 @@ extern "C" {
 
 typedef enum rapid_status {
     RAPID_OK = 0,
-    RAPID_EINVAL = -1,        /* NULL pointer, non-positive size, gamma/ctx out of range, eta < 0, T <= 0 */
+    RAPID_EINVAL = -1,        /* NULL pointer, non-positive size, gamma/ctx out of range, eta < 0, T < 0 */
     RAPID_EALIGN = -2,        /* q/k/v/out not 16-byte aligned, or a stride not a multiple of 8 elements  */
     RAPID_EUNSUPPORTED = -3,  /* head_dim not 64/128, (gamma+1)*group > 96, page size not a power of two >= 16 */
     RAPID_EWORKSPACE = -4,    /* workspace NULL, misaligned or smaller than the *_workspace_bytes() answer */
@@ -193,6 +193,12 @@ size_t rapid_accept_workspace_bytes(const rapid_ctx* ctx, int batch, int gamma_m
  *   draft_tokens  int32 [B, gamma_max]; an id outside [0, V) rejects that position
  *   gammas        int32 [B] or NULL (-> gamma_max), 0 <= gamma_b <= gamma_max
  *   eta >= 0, temperature > 0, tail_alpha >= 0 (0 disables the tail rule; the paper uses 0.1)
+ *   temperature == 0 selects the greedy limit T -> 0 of the same loop: p and q become one-hot on
+ *       the arg-max of their rows (lowest index among equal maxima), the mixing term vanishes, and
+ *       the ratio tends to infinity / 1 / 0 as the target's gap z[x_k] - max z is above / equal to /
+ *       below the drafter's gap zq[x_k] - max zq; the test stays uniforms[b,k] <= min(1, that
+ *       limit); a rejection and the bonus position emit the arg-max of target row n.  eta,
+ *       tail_alpha and uniforms[b, gamma_max] are not used.  accept_ratio holds the limit.
  *   uniforms      fp32 [B, gamma_max+1] in [0, 1)
  *   n_accepted    int32 [B]
  *   out_tokens    int32 [B, gamma_max+1]: accepted drafts, the drawn token, then -1

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "librapid.so")
-SOURCES = ["rapid_api.hip", "verify_attn.hip", "accept.hip", "hbm_probe.hip", "lm_head.hip", "kv_cache.hip", "retrieve.hip"]
+SOURCES = ["rapid_api.hip", "verify_attn.hip", "accept.hip", "accept_greedy.hip", "hbm_probe.hip", "lm_head.hip", "kv_cache.hip", "retrieve.hip"]
 # packed-fp32 instructions are switched off on purpose: some of their forms have given
 # wrong results on this hardware generation; plain fp32 code costs nothing here
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -302,7 +302,9 @@ int rapid_verify_attn_static(rapid_ctx* ctx, const rapid_attn_shape* shape,
 size_t rapid_accept_workspace_bytes(const rapid_ctx*, int batch, int gamma_max, int vocab)
 {
     if (batch < 1 || gamma_max < 0 || vocab < 1) return 0;
-    return accept_workspace_bytes(batch, gamma_max, vocab);
+    const size_t general = accept_workspace_bytes(batch, gamma_max, vocab);
+    const size_t greedy = accept_greedy_workspace_bytes(batch, gamma_max, vocab);
+    return general > greedy ? general : greedy;
 }
 
 int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
@@ -318,14 +320,16 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     if (!ctx || batch < 1 || gamma_max < 0 || vocab < 1) return RAPID_EINVAL;
     if (!target_logits || !uniforms || !n_accepted || !out_tokens) return RAPID_EINVAL;
     if (gamma_max > 0 && (!draft_logits || !draft_tokens)) return RAPID_EINVAL;
-    if (!(eta >= 0.f) || !(temperature > 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
+    if (!(eta >= 0.f) || !(temperature >= 0.f) || !(tail_alpha >= 0.f)) return RAPID_EINVAL;
     if ((target_stats && target_chunks < 1) || (draft_stats && draft_chunks < 1)) return RAPID_EINVAL;
+    const bool greedy = temperature == 0.f;                 // the limit T -> 0; row statistics have no meaning there
+    if (greedy && (target_stats || draft_stats)) return RAPID_EINVAL;
     if (batch > 65535 || gamma_max > 32767) return RAPID_EUNSUPPORTED;      // grid y / z dimensions
     if ((int64_t)batch * (gamma_max + 1) * (((int64_t)vocab + 4095) / 4096) >= ((int64_t)1 << 31)) return RAPID_EUNSUPPORTED;
     if (vocab > (1 << 22)) return RAPID_EUNSUPPORTED;                        // exchange slots of a row are staged in LDS
     if (!aligned(target_logits, 4) || !aligned(draft_logits, 4)) return RAPID_EALIGN;
     if (!aligned(target_stats, 8) || !aligned(draft_stats, 8)) return RAPID_EALIGN;
-    const size_t need = accept_workspace_bytes(batch, gamma_max, vocab);
+    const size_t need = rapid_accept_workspace_bytes(ctx, batch, gamma_max, vocab);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return RAPID_EWORKSPACE;
 
     AcceptLaunch a{};
@@ -342,7 +346,7 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     a.gmax = gamma_max;
     a.V = vocab;
     a.eta = eta;
-    a.inv_T_exact = 1.0 / (double)temperature;
+    a.inv_T_exact = greedy ? 0.0 : 1.0 / (double)temperature;
     a.inv_T = (float)a.inv_T_exact;
     a.tail_alpha = tail_alpha;
     a.ext_t = target_stats;
@@ -354,7 +358,8 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
     a.force_nv = ctx->accept_slice / 2048;
     DeviceScope dev(ctx->device);
     if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);
-    hipError_t e = launch_accept(a, static_cast<hipStream_t>(stream));
+    hipError_t e = greedy ? launch_accept_greedy(a, static_cast<hipStream_t>(stream))
+                          : launch_accept(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e);
     return RAPID_OK;
 }

@@ -65,6 +65,9 @@ struct AcceptLaunch {
 };
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int gmax, int V);
+// the greedy limit T -> 0 (accept_greedy.hip); uses zt, zd, tokens, gammas, uniforms, outputs, workspace
+hipError_t launch_accept_greedy(const AcceptLaunch& a, hipStream_t stream);
+size_t accept_greedy_workspace_bytes(int B, int gmax, int V);
 
 // ---- streaming-read probe (hbm_probe.hip)
 hipError_t configure_hbm_read_probe();

@@ -86,9 +86,12 @@ def run_accept_case(acc, *, eta, temperature=1.0, tail_alpha=0.1, use_gammas=Tru
                                           gammas=dev(gam) if gam is not None else None,
                                           temperature=float(temperature), tail_alpha=float(tail_alpha))
     torch.cuda.synchronize()
-    ref = oracle.accept(acc.target_logits, acc.draft_logits, acc.draft_tokens, acc.uniforms,
-                        eta=float(np.float32(eta)), temperature=float(np.float32(temperature)),
-                        tail_alpha=float(np.float32(tail_alpha)), gammas=gam)
+    if temperature == 0:                 # the greedy limit has its own statement in the oracle
+        ref = oracle.accept_greedy(acc.target_logits, acc.draft_logits, acc.draft_tokens, acc.uniforms, gammas=gam)
+    else:
+        ref = oracle.accept(acc.target_logits, acc.draft_logits, acc.draft_tokens, acc.uniforms,
+                            eta=float(np.float32(eta)), temperature=float(np.float32(temperature)),
+                            tail_alpha=float(np.float32(tail_alpha)), gammas=gam)
     return (n.cpu().numpy(), toks.cpu().numpy(), ratio.cpu().numpy() if ratio is not None else None), ref
 
 
@@ -108,6 +111,7 @@ def compare_accept(gpu, ref, gammas, gmax):
         stats["draw_near_ties"] += int(near_draw)
         if ratio_g is not None and g > 0:
             r, rr = ratio_g[b, :g].astype(np.float64), ref.ratio[b, :g]
+            assert np.array_equal(np.isinf(r), np.isinf(rr)), "infinite ratios must agree"
             ok = np.isfinite(rr) & (rr > 1e-30)
             if ok.any():
                 stats["max_ratio_rel_err"] = max(stats["max_ratio_rel_err"],

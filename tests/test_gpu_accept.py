@@ -161,13 +161,55 @@ def test_option_values_are_validated():
         assert e.value.status == -1
 
 
+# ---------------------------------------------------------------- the greedy limit (temperature 0)
+@pytest.mark.parametrize("V,batch,gch", [(8192, 64, (0, 1, 4)), (128256, 8, (8,)), (50257, 16, (3, 10)), (7, 32, (2,))])
+def test_greedy_limit(V, batch, gch):
+    """temperature = 0: prefix lengths, tokens and the limits of the ratios (0, 1, infinity) against the
+    oracle's statement of the T -> 0 limit, bit for bit.  Two thirds of the sequences draft the drafter's
+    arg-max (what a greedy drafter does), the rest arbitrary ids; some logits are tied on purpose."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=V, batch=batch, gamma_choices=gch, draft_noise_std=1.5, name=f"greedy_V{V}")
+    acc = wl.gen_accept_inputs(cfg, salt=5)
+    g = cfg.gamma_max
+    if g > 0:
+        acc.draft_tokens[:] = np.argmax(acc.draft_logits, -1).astype(np.int32)
+        rng = np.random.default_rng(9)
+        acc.draft_tokens[::3] = rng.integers(0, V, size=acc.draft_tokens[::3].shape)
+        acc.target_logits[1, 0, : min(V, 5)] = acc.target_logits[1, 0].max() + 1.0      # a five-way tie for the maximum
+    gpu, ref = gu.run_accept_case(acc, eta=cfg.eta, temperature=0.0)
+    np.testing.assert_array_equal(gpu[0], ref.n_accepted)
+    np.testing.assert_array_equal(gpu[1], ref.out_tokens)
+    if g > 0:
+        for b in range(batch):
+            gb = int(acc.gammas[b])
+            np.testing.assert_array_equal(gpu[2][b, :gb].astype(np.float64), ref.ratio[b, :gb])
+        assert len(set(ref.n_accepted.tolist())) >= 2
+
+
+def test_greedy_limit_counts_out_of_range_ids_and_rejects_row_statistics():
+    from paper_2502_20330_amd import binding
+    cfg = wl.scaled(wl.CONFIGS["tiny"], draft_noise_std=0.0, gamma_choices=(4,))
+    acc = wl.gen_accept_inputs(cfg, batch=2)
+    acc.draft_tokens[:] = np.argmax(acc.draft_logits, -1).astype(np.int32)
+    acc.draft_tokens[0, 2] = cfg.vocab
+    dev = lambda a: torch.from_numpy(a).cuda()
+    n, tok, _ = gu.rapid().rapid_accept(dev(acc.target_logits), dev(acc.draft_logits), dev(acc.draft_tokens), 1.0,
+                                        dev(acc.uniforms), temperature=0.0)
+    torch.cuda.synchronize()
+    assert n.tolist() == [2, 4] and gu.rapid().accept_status()[0] == 1
+    st = torch.zeros((2 * 5, 3, 2), device="cuda")
+    with pytest.raises(binding.RapidError) as e:
+        gu.rapid().rapid_accept(dev(acc.target_logits), dev(acc.draft_logits), dev(acc.draft_tokens), 1.0,
+                                dev(acc.uniforms), temperature=0.0, target_stats=st)
+    assert e.value.status == -1
+
+
 def test_bad_arguments_return_error_codes():
     from paper_2502_20330_amd import binding
     z = torch.zeros(1, 2, 8, device="cuda")
     zd = torch.zeros(1, 1, 8, device="cuda")
     t = torch.zeros(1, 1, dtype=torch.int32, device="cuda")
     u = torch.zeros(1, 2, device="cuda")
-    for kw in (dict(eta=-1.0), dict(eta=1.0, temperature=0.0), dict(eta=1.0, tail_alpha=-0.5)):
+    for kw in (dict(eta=-1.0), dict(eta=1.0, temperature=-0.5), dict(eta=1.0, tail_alpha=-0.5)):
         eta = kw.pop("eta")
         with pytest.raises(binding.RapidError) as e:
             gu.rapid().rapid_accept(z, zd, t, eta, u, **kw)
