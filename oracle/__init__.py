@@ -17,16 +17,24 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rapid_oracle.c")
-_LIB = os.path.join(_HERE, "librapid_oracle.so")
+# RAPID_ORACLE_LIB: load this shared object instead of the in-tree build (the mutation check of the
+# test suite runs the pins against deliberately broken copies of the source to show that they bite)
+_LIB = os.environ.get("RAPID_ORACLE_LIB") or os.path.join(_HERE, "librapid_oracle.so")
 _lib = None
+
+
+def compile_source(src: str, out: str) -> str:
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-o", out, src, "-lm"],
+                   check=True)
+    return out
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (float64, OpenMP over independent units)."""
+    if os.environ.get("RAPID_ORACLE_LIB"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
+        compile_source(_SRC, _LIB)
     return _LIB
 
 
@@ -51,6 +59,7 @@ def _load():
         lib.oracle_chunk_stats.restype = ctypes.c_int
         lib.oracle_kv_commit_pages.restype = ctypes.c_int
         lib.oracle_accept_greedy.restype = ctypes.c_int
+        lib.oracle_retrieval_top_k.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -304,4 +313,4 @@ def retrieve(emb, query, top_k: int, threshold: float):
 def retrieval_top_k(ctx_tokens: int, chunk_tokens: int = 512) -> int:
     """Chunks the drafter's context may hold ("RAG Setup", Sec. 3): the retrieval context is at least 4096
     tokens and otherwise 1/24 of the input, counted in whole chunks."""
-    return max(4096, ctx_tokens // 24) // chunk_tokens
+    return int(_load().oracle_retrieval_top_k(ctypes.c_int64(ctx_tokens), ctypes.c_int(chunk_tokens)))

@@ -533,6 +533,17 @@ int oracle_kv_commit_pages(int B, const int32_t* gammas, int gamma, const int32_
 
 
 /* ------------------------------------------------------------------ */
+/* Chunk budget of the drafter's context ("RAG Setup", Sec. 3): the      */
+/* retrieved context is at least 4096 tokens and otherwise 1/24 of the   */
+/* input, counted in whole chunks of chunk_tokens tokens.                */
+int oracle_retrieval_top_k(int64_t ctx_tokens, int chunk_tokens)
+{
+    if (ctx_tokens < 0 || chunk_tokens < 1) return -1;
+    int64_t budget = ctx_tokens / 24;
+    if (budget < 4096) budget = 4096;
+    return (int)(budget / chunk_tokens);
+}
+
 /* Retrieval: which chunks of the long context the drafter gets.        */
 /*   emb   float [n][dim] chunk embeddings, query float [dim]            */
 /*   sim[i] = <emb_i, query> / (|emb_i| |query|), 0 if either norm is 0  */
