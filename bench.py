@@ -228,8 +228,8 @@ def main():
     uniforms = torch.rand((B, gmax + 1), device=dev, generator=g)
     head = None
     if args.with_lm_head:
-        if B * (gmax + 1) > 16:
-            print("bench.py: --with-lm-head handles at most 16 verification rows", file=sys.stderr)
+        if B * (gmax + 1) > 96:
+            print("bench.py: --with-lm-head handles at most 96 verification rows", file=sys.stderr)
             sys.exit(2)
         g2 = torch.Generator(device=dev)
         g2.manual_seed(wl.SEED_LM_HEAD)

@@ -223,29 +223,30 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                  int32_t* n_accepted, int32_t* out_tokens, float* accept_ratio,
                  void* workspace, size_t workspace_bytes, void* stream);
 
-/* Vocabulary entries per statistics chunk of rapid_lm_head for this device and vocabulary (a multiple
- * of 16, at most 512: one chunk per workgroup, sized so that the grid fills the chip in whole rounds),
- * and the number of chunks per row, ceil(vocab / chunk).  0 if vocab < 1. */
-int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab);
-int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab);
+/* Vocabulary entries per statistics chunk of rapid_lm_head for this device, vocabulary and row count (a
+ * multiple of 16, at most 512 / ceil(n_rows / 16): one chunk per workgroup, sized so that the grid fills
+ * the chip in whole rounds), and the number of chunks per row, ceil(vocab / chunk).  0 on bad sizes. */
+int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab, int n_rows);
+int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab, int n_rows);
 
 /*
  * Output head for the verification rows: what Alg. 1 calls LogitsOf(p(. | [C; x_<j])),
  * taken as the final hidden state times the output embedding (no bias; the final
  * normalisation layer is the caller's):
  *     logits[r][v] = sum_k h[r][k] * w[v][k]      bf16 inputs, fp32 accumulation
- * and, when `stats` is given, per row and per chunk c of rapid_lm_head_chunk() consecutive entries
+ * (the weights are read once whatever the row count) and, when `stats` is given, per row and per chunk c of
+ * rapid_lm_head_chunk() consecutive entries
  *     stats[r][c] = ( max_v logits[r][v], sum_v exp((logits[r][v] - max) / temperature) )
  * which is what rapid_accept_prestats consumes (the pieces of softmax(z/T), Alg. 1).
  *
- *   n_rows       1..16 (e.g. gamma+1 rows of one sequence, ordered [sequence][position])
+ *   n_rows       1..96 (the gamma+1 rows of one sequence or of a batch, ordered [sequence][position])
  *   hidden       a multiple of 512 (multiples of 1024 take the faster path)
  *   vocab        >= 16
  *   h            bf16 [n_rows, hidden], contiguous, 16-byte aligned
  *   w            bf16 [vocab, hidden], contiguous, 16-byte aligned
  *   temperature  > 0 (used only for the statistics)
  *   logits       fp32, row r at logits + r * logits_row_stride (elements, >= vocab)
- *   stats        fp32 [n_rows, rapid_lm_head_stat_chunks(ctx, vocab), 2] or NULL
+ *   stats        fp32 [n_rows, rapid_lm_head_stat_chunks(ctx, vocab, n_rows), 2] or NULL
  * No workspace.  RAPID_EUNSUPPORTED for row counts or hidden sizes outside the above.
  */
 int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,

@@ -90,9 +90,9 @@ def load_library() -> ctypes.CDLL:
                                           f32p, ctypes.c_int, f32p, ctypes.c_int, i32p, i32p, f32p,
                                           vp, ctypes.c_size_t, vp]
     lib.rapid_accept_prestats.restype = ctypes.c_int
-    lib.rapid_lm_head_chunk.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.rapid_lm_head_chunk.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
     lib.rapid_lm_head_chunk.restype = ctypes.c_int
-    lib.rapid_lm_head_stat_chunks.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.rapid_lm_head_stat_chunks.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
     lib.rapid_lm_head_stat_chunks.restype = ctypes.c_int
     lib.rapid_lm_head.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_float,
                                   f32p, ctypes.c_int64, f32p, vp]
@@ -347,9 +347,9 @@ class Rapid:
         return sim, sel, cnt
 
     # ------------------------------------------------------------------ output head
-    def lm_head_chunk(self, vocab: int) -> int:
-        """Vocabulary entries per statistics chunk that rapid_lm_head uses for this vocabulary."""
-        return self.lib.rapid_lm_head_chunk(self._ctx, int(vocab))
+    def lm_head_chunk(self, vocab: int, n_rows: int = 1) -> int:
+        """Vocabulary entries per statistics chunk that rapid_lm_head uses for this vocabulary and row count."""
+        return self.lib.rapid_lm_head_chunk(self._ctx, int(vocab), int(n_rows))
 
     def rapid_lm_head(self, h, w, *, temperature: float = 1.0, want_stats: bool = True, logits=None, stats=None):
         """h bf16 [rows, hidden], w bf16 [vocab, hidden] -> (logits fp32 [rows, vocab],
@@ -362,7 +362,7 @@ class Rapid:
             logits = torch.empty(rows, vocab, dtype=torch.float32, device=self.device)
         assert logits.dtype == torch.float32 and logits.stride(-1) == 1 and logits.shape == (rows, vocab)
         if want_stats and stats is None:
-            stats = torch.empty(rows, self.lib.rapid_lm_head_stat_chunks(self._ctx, vocab), 2, dtype=torch.float32,
+            stats = torch.empty(rows, self.lib.rapid_lm_head_stat_chunks(self._ctx, vocab, rows), 2, dtype=torch.float32,
                                 device=self.device)
         rc = self.lib.rapid_lm_head(self._ctx, rows, hidden, vocab, _dptr(h), _dptr(w), float(temperature),
                                     _dptr(logits), logits.stride(0) if rows > 1 else vocab,

@@ -378,27 +378,30 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
 }
 
 // Vocabulary rows per workgroup of the output head: the grid should fill the chip in whole
-// rounds (one workgroup per compute unit and round), with at most 512 rows per workgroup.
-static int lm_head_blocks(const rapid_ctx* ctx, int vocab)
+// rounds (one workgroup per compute unit and round), with at most 512 / (blocks of 16 h rows) rows
+// per workgroup.
+static int lm_head_blocks(const rapid_ctx* ctx, int vocab, int n_rows)
 {
+    const int nr = n_rows < 1 ? 1 : (n_rows + 15) / 16;
+    const int64_t nbmax = 32 / (nr > 6 ? 6 : nr);
     const int64_t blocks = ((int64_t)vocab + 15) / 16;
     const int64_t n_cu = ctx ? ctx->n_cu : 256;
-    const int64_t rounds = (blocks + 32 * n_cu - 1) / (32 * n_cu);
+    const int64_t rounds = (blocks + nbmax * n_cu - 1) / (nbmax * n_cu);
     int64_t nb = (blocks + rounds * n_cu - 1) / (rounds * n_cu);
     if (nb < 1) nb = 1;
-    if (nb > 32) nb = 32;
+    if (nb > nbmax) nb = nbmax;
     return (int)nb;
 }
 
-int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab)
+int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab, int n_rows)
 {
-    return vocab < 1 ? 0 : 16 * lm_head_blocks(ctx, vocab);
+    return (vocab < 1 || n_rows < 1 || n_rows > 96) ? 0 : 16 * lm_head_blocks(ctx, vocab, n_rows);
 }
 
-int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab)
+int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab, int n_rows)
 {
-    if (vocab < 1) return 0;
-    const int chunk = 16 * lm_head_blocks(ctx, vocab);
+    if (vocab < 1 || n_rows < 1 || n_rows > 96) return 0;
+    const int chunk = 16 * lm_head_blocks(ctx, vocab, n_rows);
     return (vocab + chunk - 1) / chunk;
 }
 
@@ -408,7 +411,7 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
 {
     if (!ctx || !h || !w || !logits) return RAPID_EINVAL;
     if (n_rows < 1 || hidden < 1 || vocab < 1 || logits_row_stride < vocab || !(temperature > 0.f)) return RAPID_EINVAL;
-    if (n_rows > 16 || hidden % 512 || vocab < 16) return RAPID_EUNSUPPORTED;
+    if (n_rows > 96 || hidden % 512 || vocab < 16) return RAPID_EUNSUPPORTED;
     if (!aligned(h, 16) || !aligned(w, 16) || !aligned(logits, 4) || !aligned(stats, 8)) return RAPID_EALIGN;
     LmHeadLaunch a{};
     a.h = static_cast<const uint16_t*>(h);
@@ -419,7 +422,7 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
     a.hidden = hidden;
     a.vocab = vocab;
     a.ldz = logits_row_stride;
-    a.nb = lm_head_blocks(ctx, vocab);
+    a.nb = lm_head_blocks(ctx, vocab, n_rows);
     a.inv_T = (float)(1.0 / (double)temperature);
     DeviceScope dev(ctx->device);
     if (dev.err != hipSuccess) return hip_fail(ctx, dev.err);

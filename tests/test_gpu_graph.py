@@ -45,7 +45,7 @@ def test_captured_round_replays_identically():
             torch.zeros(cfg.batch, cfg.q_max, dtype=torch.int32, device="cuda"),
             torch.zeros(cfg.batch, cfg.gamma_max, dtype=torch.float32, device="cuda"))
     logits = torch.empty(5, 3000, dtype=torch.float32, device="cuda")
-    stats = torch.empty(5, r.lib.rapid_lm_head_stat_chunks(r._ctx, 3000), 2, dtype=torch.float32, device="cuda")
+    stats = torch.empty(5, r.lib.rapid_lm_head_stat_chunks(r._ctx, 3000, 5), 2, dtype=torch.float32, device="cuda")
 
     def round_():
         r.rapid_kv_append(k, v, kn, vn, ctx, gammas=gam, page_table=pt, max_ctx=s.max_ctx)

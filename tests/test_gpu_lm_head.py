@@ -43,8 +43,8 @@ def run(rows, hidden, vocab, T=1.0, salt=0, what=""):
     worst = np.unravel_index(np.argmax(err - RTOL * np.abs(ref)), err.shape)
     assert np.all(err <= ATOL + RTOL * np.abs(ref)), \
         f"{what}: max abs err {err.max():.3e} at {worst}: got {z[worst]:.6f} ref {ref[worst]:.6f}"
-    CH = gu.rapid().lm_head_chunk(vocab)                    # chunk the library chose for this vocabulary
-    assert CH % 16 == 0 and 16 <= CH <= 512
+    CH = gu.rapid().lm_head_chunk(vocab, rows)              # chunk the library chose for this vocabulary and row count
+    assert CH % 16 == 0 and 16 <= CH <= 512 // ((rows + 15) // 16)
     nch = (vocab + CH - 1) // CH
     assert st.shape == (rows, nch, 2)
     # chunk maxima: exactly the maxima of the logits the kernel wrote
@@ -65,9 +65,15 @@ def test_vocabulary_edges(vocab):
     run(9, 1024, vocab, what=f"vocab{vocab}")
 
 
-@pytest.mark.parametrize("rows", [1, 2, 5, 9, 11, 16])
+@pytest.mark.parametrize("rows", [1, 2, 5, 9, 11, 16, 17, 31, 32, 33, 48, 55, 64, 72, 80, 81, 96])
 def test_row_counts(rows):
+    """One to six blocks of 16 rows of h over one pass of the weights (a batch of verification steps)."""
     run(rows, 2048, 3000, salt=rows, what=f"rows{rows}")
+
+
+@pytest.mark.parametrize("rows,hidden,vocab", [(72, 3584, 5000), (40, 1536, 777), (96, 4096, 16), (20, 512, 8193)])
+def test_many_rows_on_other_widths_and_vocabulary_edges(rows, hidden, vocab):
+    run(rows, hidden, vocab, salt=rows + hidden, what=f"rows{rows}_hidden{hidden}_vocab{vocab}")
 
 
 @pytest.mark.parametrize("hidden", [512, 1024, 1536, 3072, 3584, 4096, 5120, 8192])
@@ -105,11 +111,11 @@ def test_repeat_calls_are_bitwise_identical():
 
 def test_bad_arguments_return_error_codes():
     r = gu.rapid()
-    h = torch.zeros(17, 1024, dtype=torch.bfloat16, device="cuda")
+    h = torch.zeros(97, 1024, dtype=torch.bfloat16, device="cuda")
     w = torch.zeros(64, 1024, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(binding.RapidError) as e:
-        r.rapid_lm_head(h, w)
-    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # 17 rows
+        r.rapid_lm_head(h, w, want_stats=False)
+    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # 97 rows
     with pytest.raises(binding.RapidError) as e:
         r.rapid_lm_head(h[:4, :1000].contiguous(), w[:, :1000].contiguous())
     assert e.value.status == binding.RAPID_EUNSUPPORTED                      # hidden not a multiple of 512
@@ -160,6 +166,30 @@ def test_full_size_head_and_accept_with_its_statistics():
         print(f"[head+accept eta={eta}] n_accepted={int(b[0][0])} tokens={b[1][0].tolist()}")
         accepted.append(int(b[0][0]))
     assert max(accepted) > 0, "the correlated drafter should get some drafts accepted"
+
+
+def test_batched_head_feeds_the_batched_accept():
+    """The ragged batch of the benchmark (8 sequences, gamma in {4, 6, 8}: 72 row slots): one pass over the
+    LLaMA-sized weights gives all target logits and their statistics, which rapid_accept_prestats consumes;
+    every logit against the oracle, and the accept results against the oracle's accept on the same logits."""
+    cfg = wl.CONFIGS["ragged_paged"]
+    seqs = wl.gen_sequences(cfg)
+    B, g, V = cfg.batch, cfg.gamma_max, cfg.vocab
+    rows = B * (g + 1)
+    z, st, _ = run(rows, 4096, V, what="batched head")
+    zt = z.astype(np.float32).reshape(B, g + 1, V)
+    rng = np.random.default_rng(17)
+    zd = (zt[:, :g] + rng.standard_normal((B, g, V)).astype(np.float32)).astype(np.float32)
+    tok = np.argmax(zd.astype(np.float64) + rng.gumbel(size=zd.shape), -1).astype(np.int32)
+    u = rng.random((B, g + 1)).astype(np.float32)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got = gu.rapid().rapid_accept(dev(zt), dev(zd), dev(tok), cfg.eta, dev(u), gammas=dev(seqs.gammas),
+                                  target_stats=st_dev(st))
+    torch.cuda.synchronize()
+    ref = oracle.accept(zt, zd, tok, u, eta=cfg.eta, gammas=seqs.gammas)
+    res = gu.compare_accept(tuple(x.cpu().numpy() for x in got), ref, seqs.gammas, g)
+    assert res["n_mismatch"] == 0 and res["token_mismatch"] == 0 and res["exempt_sequences"] == 0, res
+    assert res["max_ratio_rel_err"] < 1e-4, res
 
 
 def st_dev(st):
