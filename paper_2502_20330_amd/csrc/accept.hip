@@ -18,8 +18,8 @@
 //       registers.  It publishes the slice's (max, sum exp) of either row, picks up the
 //       publications of the other workgroups of the row pair, and with the row normalisers
 //       forms d = z/T + eta (q - p) for its slice (still in registers) and publishes
-//       (max d, sum exp(d - max)).  The workgroup that arrives last at a row combines all
-//       slices in fp64 and runs the accept test of the drafted token.
+//       (max d, sum exp(d - max)).  The workgroup of slice 0 then collects all slices of its row,
+//       combines them in fp64 and runs the accept test of the drafted token.
 //
 //   accept_draw_row   n = first rejected position; the draw weights of row n (the residual,
 //       or p of the bonus row) are formed entirely in fp64 -- exponentials, normalisers,
@@ -171,13 +171,12 @@ struct Ws {
     u64* slot_d;      // [B][gmax][wmax]
     u64* slot_h;      // [B][gmax][wmax]    (max d, sum exp2(d - max)), d in log2 units relative to zmax_t/T
     u64* slot_b;      // [B][w2][6]         fp64 exchange words of accept_draw_row
-    int32_t* arrive;  // [B][gmax+1]        workgroups of a row that have published everything
     double* rows;     // [B][gmax+1][4]: zmax_t, zmax_d (raw maxima, exact)
     int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
     int wmax;         // slots per row (slices of the smallest slice size)
     int w2;           // workgroups per sequence in accept_draw_row
     size_t n_empty;   // u64 words from slot_t that start "empty"
-    size_t n_zero;    // int32 words from status / arrive that start at zero (two ranges)
+    size_t n_zero;    // int32 words from status that start at zero
     size_t bytes;
 };
 
@@ -191,7 +190,6 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
     w.w2 = (V + kDrawSlice - 1) / kDrawSlice;
     char* p = static_cast<char*>(base);
     w.status = reinterpret_cast<int32_t*>(p); p += 256;
-    w.arrive = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * (gmax + 1) * sizeof(int32_t));
     w.n_zero = (size_t)(p - static_cast<char*>(base)) / sizeof(int32_t);
     char* e0 = p;
     w.slot_t = reinterpret_cast<u64*>(p); p += align256((size_t)B * (gmax + 1) * w.wmax * sizeof(u64));
@@ -208,7 +206,7 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
 __global__ void __launch_bounds__(256) accept_init(Ws ws)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, n = (size_t)gridDim.x * 256;
-    for (size_t j = i; j < ws.n_zero; j += n) ws.status[j] = 0;          // status and arrive are adjacent
+    for (size_t j = i; j < ws.n_zero; j += n) ws.status[j] = 0;
     for (size_t j = i; j < ws.n_empty; j += n) ws.slot_t[j] = kEmpty;    // all slot arrays are adjacent
 }
 
@@ -404,7 +402,6 @@ __device__ __forceinline__ void wave_combine_f64(Pair pair, int n, double scale,
 struct LdsA {
     float red[4 * kWaves];
     PairNorm norm;
-    int last;
     int nmiss;
     u64 slots[];          // 2 W words: target slices, draft slices; later the W shifted slices
 };
@@ -541,11 +538,9 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
             STAMP_AT(id, 4);
         }
 
-        // ---- the last workgroup to arrive at this row decides it
-        if (tid == 0) lds.last = atomicAdd(ws.arrive + (int64_t)b * rows + k, 1) == W - 1;
-        __syncthreads();
+        // ---- the workgroup of slice 0 decides the row once all slices have reported
         STAMP_AT(id, 5);
-        if (lds.last) {
+        if (w == 0) {
             // Wave 0 first fetches the drafted token's two logits (a dependent chain that overlaps the polls).
             int xtok = -1;
             float zx_t = 0.f, zx_d = 0.f;
@@ -715,7 +710,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
     const double Mt = rec[0], Md = rec[1], invT = a.inv_T_exact;
 
     // own slice: e_t, e_d of the thread's entries, kept in registers for all phases
-    double et[NE], ed[NE];
+    double et[NE], ed[NE], wgt[NE];
     const int64_t first = (int64_t)w * kSlice + (int64_t)tid * NE;
 #pragma unroll
     for (int v = 0; v < NE / 4; ++v) {
@@ -726,6 +721,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         for (int j = 0; j < 4; ++j) {
             et[v * 4 + j] = exp_c(((double)t4[j] - Mt) * invT);
             ed[v * 4 + j] = bonus ? 0.0 : exp_c(((double)d4[j] - Md) * invT);
+            wgt[v * 4 + j] = 0.0;
         }
     }
     STAMP(9);
@@ -749,7 +745,16 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
     for (int phase = 1; phase <= nphase; ++phase) {
         double a0 = 0.0, a1 = phase == 2 ? -INFINITY : 0.0;
 #pragma unroll
-        for (int i = 0; i < NE; ++i) draw_accumulate(phase, et[i], ed[i], nm, a0, a1);
+        for (int i = 0; i < NE; ++i) {
+            if (phase == 3) {                                 // the weights are kept for the token search
+                double p;
+                wgt[i] = draw_weight(et[i], ed[i], nm, p);
+                a0 += wgt[i];
+                a1 += p;
+            } else {
+                draw_accumulate(phase, et[i], ed[i], nm, a0, a1);
+            }
+        }
         if (phase == 2) block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpMaxD());
         else block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpAddD());
         u64* base = my_slots + (phase - 1) * 2;              // slice s: words base[6 s], base[6 s + 1]
@@ -837,12 +842,11 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
 
     // ---- this workgroup's range holds the crossing: running sums in vocabulary order = thread order
     if (tid == 0) { lds.pick_lo = 0x7fffffff; lds.pick_hi = -1; }
-    double wgt[NE], seg = 0.0;
+    double seg = 0.0;
 #pragma unroll
     for (int i = 0; i < NE; ++i) {
-        double p;
-        const double wr = (bonus || word == 1) ? 0.0 : draw_weight(et[i], ed[i], nm, p);
-        wgt[i] = bonus ? et[i] : (word == 1 ? et[i] * nm.iSt : wr);
+        if (bonus) wgt[i] = et[i];
+        else if (word == 1) wgt[i] = et[i] * nm.iSt;           // (else: the residual weight from phase 3)
         seg += wgt[i];
     }
     const double incl = wave_scan(seg, OpAddD());
