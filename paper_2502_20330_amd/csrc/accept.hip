@@ -170,7 +170,7 @@ struct Ws {
     u64* slot_t;      // [B][gmax+1][wmax]  (raw max, sum exp((z-max)/T)) per slice of a target row
     u64* slot_d;      // [B][gmax][wmax]
     u64* slot_h;      // [B][gmax][wmax]    (max d, sum exp2(d - max)), d in log2 units relative to zmax_t/T
-    u64* slot_b;      // [B][w2][6]         fp64 exchange words of accept_draw_row
+    u64* slot_b;      // [B][3][w2][2]      fp64 exchange words of accept_draw_row, per phase
     double* rows;     // [B][gmax+1][4]: zmax_t, zmax_d (raw maxima, exact)
     int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
     int wmax;         // slots per row (slices of the smallest slice size)
@@ -646,7 +646,6 @@ struct DrawNorm { double iSt, iSd, iSh, thr, eta; };
 struct LdsB {
     double red[4 * kWaves];
     int nmiss;
-    int pick_lo, pick_hi;
     u64 slots[];          // 2 W2 words: the two sums of every slice for the current phase
 };
 
@@ -757,10 +756,9 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         }
         if (phase == 2) block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpMaxD());
         else block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpAddD());
-        u64* base = my_slots + (phase - 1) * 2;              // slice s: words base[6 s], base[6 s + 1]
-        if (tid == 0) { slot_store(base + 6 * w, pack_d(a0)); slot_store(base + 6 * w + 1, pack_d(a1)); }
-        if (tid < 64) poll_into([&](int i) { return base + 6 * (i >> 1) + (i & 1); }, 0, 2 * W2, lds.slots, &lds.nmiss,
-                                a.wait_ticks);
+        u64* base = my_slots + (phase - 1) * 2 * W2;         // slice s: words base[2 s], base[2 s + 1]
+        if (tid == 0) { slot_store(base + 2 * w, pack_d(a0)); slot_store(base + 2 * w + 1, pack_d(a1)); }
+        if (tid < 64) poll_into([&](int i) { return base + i; }, 0, 2 * W2, lds.slots, &lds.nmiss, a.wait_ticks);
         __syncthreads();
         if (__builtin_expect(lds.nmiss != 0, 0)) {
             // a slice whose sums did not arrive: the same sums from the logits in memory
@@ -782,8 +780,8 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
                     if (v1 == kEmpty) v1 ^= 1ull;
                     lds.slots[2 * s] = v0;
                     lds.slots[2 * s + 1] = v1;
-                    slot_store(base + 6 * s, v0);
-                    slot_store(base + 6 * s + 1, v1);
+                    slot_store(base + 2 * s, v0);
+                    slot_store(base + 2 * s + 1, v1);
                     atomicAdd(ws.status + 1, 1);
                 }
                 __syncthreads();
@@ -841,7 +839,6 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
     if (owner != w) return;
 
     // ---- this workgroup's range holds the crossing: running sums in vocabulary order = thread order
-    if (tid == 0) { lds.pick_lo = 0x7fffffff; lds.pick_hi = -1; }
     double seg = 0.0;
 #pragma unroll
     for (int i = 0; i < NE; ++i) {
@@ -864,11 +861,18 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         }
         run = nxt;
     }
-    if (my_hi >= 0) atomicMax(&lds.pick_hi, my_hi);
-    if (my_lo != 0x7fffffff) atomicMin(&lds.pick_lo, my_lo);
+    // entries are in thread order: the first thread with a hit holds the smallest index, the last
+    // thread with weight the largest (ballots instead of atomics on one LDS word)
+    const unsigned long long hit = __ballot(my_lo != 0x7fffffff), any = __ballot(my_hi >= 0);
+    const int lo_w = hit ? __shfl(my_lo, __ffsll((long long)hit) - 1) : 0x7fffffff;
+    const int hi_w = any ? __shfl(my_hi, 63 - __clzll((long long)any)) : -1;
+    int* picks = reinterpret_cast<int*>(lds.red + 2 * kWaves);    // [kWaves][2], past the wave totals above
+    if (lane == 0) { picks[2 * wave] = lo_w; picks[2 * wave + 1] = hi_w; }
     __syncthreads();
     if (tid == 0) {
-        const int tok = lds.pick_lo != 0x7fffffff ? lds.pick_lo : lds.pick_hi;   // pick_hi: rounding at the slice's end
+        int lo = 0x7fffffff, hi = -1;
+        for (int s = 0; s < kWaves; ++s) { lo = min(lo, picks[2 * s]); hi = max(hi, picks[2 * s + 1]); }
+        const int tok = lo != 0x7fffffff ? lo : hi;           // hi: rounding at the slice's end
         a.out_tokens[(int64_t)b * (a.gmax + 1) + n] = tok;
     }
     STAMP(14);
