@@ -210,6 +210,13 @@ size_t rapid_accept_workspace_bytes(const rapid_ctx* ctx, int batch, int gamma_m
  *                       rejected because the id was outside [0, V)
  *                   [RAPID_ACCEPT_STATUS_GIVEUPS]  diagnostics: exchange waits of this call that
  *                       ran into RAPID_OPT_ACCEPT_WAIT_US (results are unaffected)
+ *                 Ownership: the workspace may hold anything when it is first used and is never
+ *                 cleared by the library, but between two calls that use it the caller must either
+ *                 leave all of it untouched or fill all of it with zeros: its head also holds a
+ *                 counter that moves with every execution (replays of a captured HIP graph
+ *                 included), and a call recognises what its own workgroups exchanged through the
+ *                 workspace by tags derived from that counter.  Two calls that share a workspace
+ *                 must not overlap in time.
  * vocab <= 2^22.  Logit rows whose address is not 16-byte aligned (vocab not a multiple of 4)
  * are read with scalar loads: same results, lower bandwidth.
  */

@@ -141,6 +141,7 @@ class Rapid:
         torch.cuda.set_device(self.device)
         _check(self.lib, self.lib.rapid_create(ctypes.byref(self._ctx), device))
         self._ws: Optional[torch.Tensor] = None
+        self._ws_accept: Optional[torch.Tensor] = None
         self._sink: Optional[torch.Tensor] = None
 
     def close(self):
@@ -161,13 +162,19 @@ class Rapid:
         """(rejected out-of-range draft ids, exchange waits that gave up) of the last rapid_accept call that
         used this object's workspace; synchronises."""
         torch.cuda.synchronize(self.device)
-        w = self._ws[:8].view(torch.int32).cpu()
+        w = self._ws_accept[:8].view(torch.int32).cpu()
         return int(w[0]), int(w[1])
 
     def _workspace(self, nbytes: int) -> torch.Tensor:
         if self._ws is None or self._ws.numel() < nbytes:
             self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
         return self._ws
+
+    def _accept_workspace(self, nbytes: int) -> torch.Tensor:
+        # its own buffer: the accept pass keeps a call counter in it from one call to the next
+        if self._ws_accept is None or self._ws_accept.numel() < nbytes:
+            self._ws_accept = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        return self._ws_accept
 
     # ------------------------------------------------------------------ attention
     def attn_shape(self, q, k_cache, ctx_max: int, *, gamma: Optional[int] = None, page_table=None,
@@ -267,7 +274,7 @@ class Rapid:
         else:
             n_acc, toks, ratio = outs
         need = self.lib.rapid_accept_workspace_bytes(self._ctx, B, g, V)
-        ws = self._workspace(need)
+        ws = self._accept_workspace(need)
         if target_stats is None and draft_stats is None:
             rc = self.lib.rapid_accept(self._ctx, B, g, V, _dptr(target_logits), _dptr(draft_logits),
                                        _dptr(draft_tokens), _dptr(gammas), float(eta), float(temperature),

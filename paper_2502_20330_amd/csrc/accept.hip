@@ -9,9 +9,7 @@
 //
 // The accept test of a position needs p, q, p_hat only at the one drafted token, given three
 // log-normalisers per row; only the row where the draw happens needs an elementwise pass.
-// Three launches:
-//
-//   accept_init   fills the exchange slots of the workspace with the "empty" pattern.
+// Two launches:
 //
 //   accept_rows   reads every logit ONCE.  A row pair (target row k, draft row k) is cut into
 //       slices of 2048*NV entries; one workgroup of 512 threads holds its slice of both rows in
@@ -27,13 +25,20 @@
 //       between the workgroups of the row (normalisers of p and q; normaliser and maximum
 //       of p_hat; weight totals), then the workgroup whose range holds u*W finds the token.
 //
-// Exchange between workgroups.  A publication is one 64-bit word written with a device-scope
-// atomic store into a slot that accept_init set to all ones; a reader polls the slot with
-// device-scope atomic loads until it is no longer empty.  Every wait is bounded (wall-clock
-// ticks): when a slot stays empty, the waiting workgroup computes that slice's publication
-// itself from the logits in memory -- same code, same order of operations, hence the same
-// bits -- stores it into the slot, and goes on.  No workgroup ever depends on another one
-// for termination, and results do not depend on timing.
+// Exchange between workgroups.  A publication is a group of 64-bit words, each written with a
+// device-scope atomic store: 32 bits of payload below a 32-bit tag.  The two tags (even and odd
+// words) belong to the call: they are derived from a counter in the workspace that the other
+// kernel of the pass advances, so it is constant while a kernel runs and differs from every
+// earlier execution's, also when a captured graph replays the launches.  A reader polls the
+// words with device-scope atomic loads until every tag is the call's.  An earlier call's
+// publications never carry them; whatever else a workspace holds when it is first used is taken
+// for a publication only if both tags of a pair match, 2^-64 for unrelated bits.  Nothing has to
+// be cleared before the pass, hence no third launch; in return the caller must leave the
+// workspace alone between calls (or zero all of it).  Every wait is
+// bounded (wall-clock ticks): when a word stays unpublished, the waiting workgroup computes that
+// slice's publication itself from the logits in memory -- same code, same order of operations,
+// hence the same bits -- stores it, and goes on.  No workgroup ever depends on another one for
+// termination, and results do not depend on timing.
 //
 // Numerics: per-slice sums in fp32, combined in fp32 for the elementwise pass of accept_rows
 // and in fp64 for every decision; the accept ratio therefore carries ~1e-7 relative error
@@ -64,7 +69,6 @@ constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kDrawSlice = kThreads * 8;            // smallest slice of accept_draw_row (8 entries per thread)
 constexpr int kMinSlice = kThreads * 4 * 2;         // smallest slice of accept_rows (NV = 2)
-constexpr u64 kEmpty = ~0ull;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr double kLn2 = 0.6931471805599453;
 
@@ -167,18 +171,19 @@ __device__ __forceinline__ int seq_gamma(const AcceptLaunch& a, int b)
 struct Ws {
     int32_t* status;  // [64]: [0] positions rejected because the draft id was outside [0, V)
                       //       [1] exchange waits that gave up and recomputed the missing slice
-    u64* slot_t;      // [B][gmax+1][wmax]  (raw max, sum exp((z-max)/T)) per slice of a target row
-    u64* slot_d;      // [B][gmax][wmax]
-    u64* slot_h;      // [B][gmax][wmax]    (max d, sum exp2(d - max)), d in log2 units relative to zmax_t/T
-    u64* slot_b;      // [B][3][w2][2]      fp64 exchange words of accept_draw_row, per phase
+                      //       [kCntRows] / [kCntDraw] call counters read by accept_rows / accept_draw_row
+                      //       [kGiveRows], [kGiveRows + 1] give-ups of accept_rows: count, tag of the call
+    u64* slot_t;      // [B][gmax+1][wmax][2]  (raw max, sum exp((z-max)/T)) per slice of a target row
+    u64* slot_d;      // [B][gmax][wmax][2]
+    u64* slot_h;      // [B][gmax][wmax][2]    (max d, sum exp2(d - max)), d in log2 units relative to zmax_t/T
+    u64* slot_b;      // [B][3][w2][4]         two fp64 values per slice and phase of accept_draw_row
     double* rows;     // [B][gmax+1][4]: zmax_t, zmax_d (raw maxima, exact)
-    int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test
+    int32_t* flags;   // [B][gmax]: 1 = draft k passed its accept test, 2 = its id was outside [0, V)
     int wmax;         // slots per row (slices of the smallest slice size)
     int w2;           // workgroups per sequence in accept_draw_row
-    size_t n_empty;   // u64 words from slot_t that start "empty"
-    size_t n_zero;    // int32 words from status that start at zero
     size_t bytes;
 };
+constexpr int kCntRows = 8, kCntDraw = 9, kGiveRows = 10;
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
@@ -190,24 +195,14 @@ __host__ __device__ inline Ws carve(void* base, int B, int gmax, int V)
     w.w2 = (V + kDrawSlice - 1) / kDrawSlice;
     char* p = static_cast<char*>(base);
     w.status = reinterpret_cast<int32_t*>(p); p += 256;
-    w.n_zero = (size_t)(p - static_cast<char*>(base)) / sizeof(int32_t);
-    char* e0 = p;
-    w.slot_t = reinterpret_cast<u64*>(p); p += align256((size_t)B * (gmax + 1) * w.wmax * sizeof(u64));
-    w.slot_d = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * sizeof(u64));
-    w.slot_h = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * sizeof(u64));
-    w.slot_b = reinterpret_cast<u64*>(p); p += align256((size_t)B * w.w2 * 6 * sizeof(u64));
-    w.n_empty = (size_t)(p - e0) / sizeof(u64);
+    w.slot_t = reinterpret_cast<u64*>(p); p += align256((size_t)B * (gmax + 1) * w.wmax * 2 * sizeof(u64));
+    w.slot_d = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * 2 * sizeof(u64));
+    w.slot_h = reinterpret_cast<u64*>(p); p += align256((size_t)B * gd * w.wmax * 2 * sizeof(u64));
+    w.slot_b = reinterpret_cast<u64*>(p); p += align256((size_t)B * w.w2 * 12 * sizeof(u64));
     w.rows = reinterpret_cast<double*>(p); p += align256((size_t)B * (gmax + 1) * 4 * sizeof(double));
     w.flags = reinterpret_cast<int32_t*>(p); p += align256((size_t)B * gd * sizeof(int32_t));
     w.bytes = (size_t)(p - static_cast<char*>(base));
     return w;
-}
-
-__global__ void __launch_bounds__(256) accept_init(Ws ws)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, n = (size_t)gridDim.x * 256;
-    for (size_t j = i; j < ws.n_zero; j += n) ws.status[j] = 0;
-    for (size_t j = i; j < ws.n_empty; j += n) ws.slot_t[j] = kEmpty;    // all slot arrays are adjacent
 }
 
 // ---------------------------------------------------------------- exchange primitives
@@ -217,17 +212,49 @@ __device__ __forceinline__ u64 slot_load(const u64* p)
 }
 __device__ __forceinline__ void slot_store(u64* p, u64 v)
 {
-    if (v == kEmpty) v ^= 1ull;                      // never publish the "empty" pattern itself
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ u64 pack2f(float a, float b)
+// The call's tags: words at even offsets of a slot array carry t0, words at odd offsets t1.  Each is
+// one-to-one (odd multiplier) in the call counter kept in the workspace, which moves by one with every
+// execution of the pass, replays of a captured graph included: no two executions within 2^32 on one
+// workspace share either tag.  A zero-filled workspace (counter 0, tags 0 in every slot) is safe too:
+// neither tag of counter 0 is zero.
+struct Tags { uint32_t t0, t1; };
+__device__ __forceinline__ Tags make_tags(uint32_t counter)
 {
-    return (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
+    return Tags{counter * 0x9E3779B1u + 0x7F4A7C15u, (counter * 0x85EBCA77u) ^ 0xC2B2AE3Du};
 }
+__device__ __forceinline__ bool word_ok(u64 v, int i, const Tags& t) { return (uint32_t)(v >> 32) == ((i & 1) ? t.t1 : t.t0); }
+__device__ __forceinline__ u64 tagged(uint32_t payload, uint32_t tag) { return (u64)payload | ((u64)tag << 32); }
 __device__ __forceinline__ float lo_f(u64 v) { return __uint_as_float((uint32_t)v); }
-__device__ __forceinline__ float hi_f(u64 v) { return __uint_as_float((uint32_t)(v >> 32)); }
-__device__ __forceinline__ u64 pack_d(double d) { return (u64)__double_as_longlong(d); }
-__device__ __forceinline__ double unpack_d(u64 v) { return __longlong_as_double((long long)v); }
+// Two floats = one slot of two words; p must be an even offset into its array.
+__device__ __forceinline__ void publish2f(u64* p, float a, float b, const Tags& t)
+{
+    slot_store(p, tagged(__float_as_uint(a), t.t0));
+    slot_store(p + 1, tagged(__float_as_uint(b), t.t1));
+}
+// One double = two words (high half first).
+__device__ __forceinline__ void put_d(u64* p, double d, const Tags& t, bool global)
+{
+    const u64 x = (u64)__double_as_longlong(d);
+    const u64 hi = tagged((uint32_t)(x >> 32), t.t0), lo = tagged((uint32_t)x, t.t1);
+    if (global) { slot_store(p, hi); slot_store(p + 1, lo); }
+    else { p[0] = hi; p[1] = lo; }
+}
+__device__ __forceinline__ double get_d(const u64* p)
+{
+    return __longlong_as_double((long long)(((p[0] & 0xffffffffull) << 32) | (p[1] & 0xffffffffull)));
+}
+// Rarely taken: count a give-up of accept_rows in a (count, tag) pair that needs no clearing.
+__device__ __forceinline__ void count_giveup(int32_t* status, const Tags& t)
+{
+    u64* p = reinterpret_cast<u64*>(status + kGiveRows);
+    u64 old = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+        const u64 nw = (uint32_t)(old >> 32) == t.t0 ? old + 1 : tagged(1u, t.t0);
+        if (__hip_atomic_compare_exchange_strong(p, &old, nw, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+    }
+}
 
 // Compact fp64 exponential (about twenty instructions, inlined where used): exp(x) with ~2e-16
 // relative error for x <= 700; anything below -745 (also -inf and NaN) gives 0.  The decisions
@@ -255,29 +282,35 @@ __device__ __forceinline__ double exp_c(double x)
     p = fma(p, r, 1.0);
     return ldexp(p, (int)k);
 }
-// Wave 0: poll the slots addr(lo) .. addr(hi - 1) into dst[lo .. hi) until none is empty or
-// `wait_ticks` have passed; *nmiss = slots still empty (left as kEmpty in dst).
+// Wave 0: poll the words addr(lo) .. addr(hi - 1) into dst[lo .. hi) until every one carries its
+// tag or `wait_ticks` have passed; *nmiss = words still unpublished (dst then holds what was there).
+// lo and hi are even and addr(i) has the parity of i.  Two words per lane and round.
 template <class Addr>
-__device__ __forceinline__ void poll_into(Addr addr, int lo, int hi, u64* dst, int* nmiss, int64_t wait_ticks)
+__device__ __forceinline__ void poll_into(Addr addr, int lo, int hi, u64* dst, int* nmiss, int64_t wait_ticks, const Tags& tg)
 {
     const int lane = threadIdx.x;
     const int64_t t0 = (int64_t)wall_clock64();
     int miss = 0;
-    for (int i0 = lo; i0 < hi; i0 += 64) {
-        const int i = i0 + lane;
-        u64 v = kEmpty;
-        bool pending = i < hi;
+    for (int i0 = lo; i0 < hi; i0 += 128) {
+        const int ia = i0 + lane, ib = ia + 64;
+        u64 va = 0, vb = 0;
+        bool pa = ia < hi, pb = ib < hi;
         for (;;) {
-            if (pending) {
-                v = slot_load(addr(i));
-                pending = v == kEmpty;
+            if (pa) {
+                va = slot_load(addr(ia));
+                pa = !word_ok(va, ia, tg);
             }
-            if (!__any(pending)) break;
+            if (pb) {
+                vb = slot_load(addr(ib));
+                pb = !word_ok(vb, ib, tg);
+            }
+            if (!__any(pa || pb)) break;
             if ((int64_t)wall_clock64() - t0 >= wait_ticks) break;
             __builtin_amdgcn_s_sleep(2);
         }
-        if (i < hi) dst[i] = v;
-        miss += __popcll(__ballot(pending));
+        if (ia < hi) dst[ia] = va;
+        if (ib < hi) dst[ib] = vb;
+        miss += __popcll(__ballot(pa)) + __popcll(__ballot(pb));
     }
     if (lane == 0) *nmiss = miss;
 }
@@ -403,7 +436,7 @@ struct LdsA {
     float red[4 * kWaves];
     PairNorm norm;
     int nmiss;
-    u64 slots[];          // 2 W words: target slices, draft slices; later the W shifted slices
+    u64 slots[];          // 6 W words: two per slice of the target row, the draft row, the shifted row
 };
 
 // ---------------------------------------------------------------- accept_rows
@@ -454,7 +487,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
     };
 
     // Everything after the loads of one item.
-    auto process = [&](int id, int g, floatx4 (&x)[NV], floatx4 (&y)[NV]) {
+    auto process = [&](int id, int g, floatx4 (&x)[NV], floatx4 (&y)[NV], const Tags& tg) {
         const int w = id % W, k = (id / W) % rows, b = id / (W * rows);
         if (k > g) return;
         STAMP_AT(id, 1);
@@ -464,9 +497,9 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
         const bool vec_t = (reinterpret_cast<uintptr_t>(zt) & 15) == 0;
         const bool vec_d = (reinterpret_cast<uintptr_t>(zd) & 15) == 0;
         const bool own_t = a.ext_t == nullptr, own_d = pair && a.ext_d == nullptr;
-        u64* slot_t = ws.slot_t + ((int64_t)b * rows + k) * ws.wmax;
-        u64* slot_d = ws.slot_d + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax;
-        u64* slot_h = ws.slot_h + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax;
+        u64* slot_t = ws.slot_t + ((int64_t)b * rows + k) * ws.wmax * 2;
+        u64* slot_d = ws.slot_d + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax * 2;
+        u64* slot_h = ws.slot_h + ((int64_t)b * a.gmax + (pair ? k : 0)) * ws.wmax * 2;
         auto reg_t = [&](int v) { return x[v]; };
         auto reg_d = [&](int v) { return y[v]; };
         // slice s of either row straight from memory (a slice another workgroup owns)
@@ -479,30 +512,36 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
             float mt, st, md, sd;
             slice_stats<NV, true>(reg_t, reg_d, own_t, own_d, c, lds.red, bank, mt, st, md, sd);
             if (tid == 0) {
-                if (own_t) slot_store(slot_t + w, pack2f(mt, st));
-                if (own_d) slot_store(slot_d + w, pack2f(md, sd));
+                if (own_t) publish2f(slot_t + 2 * w, mt, st, tg);
+                if (own_d) publish2f(slot_d + 2 * w, md, sd, tg);
             }
         }
         STAMP_AT(id, 2);
 
-        // ---- publications of all slices of the row (pair): lds.slots[0..W) target, [W..2W) draft.
-        // A slice that stays empty past the bound is computed here (and published for the others).
+        // ---- publications of all slices of the row (pair): lds.slots[0..2W) target, [2W..4W) draft.
+        // A slice that stays unpublished past the bound is computed here (and published for the others).
         u64* got = lds.slots;
+        const int W2w = 2 * W;
+        auto have = [&](const u64* g2, int s) { return word_ok(g2[2 * s], 0, tg) && word_ok(g2[2 * s + 1], 1, tg); };
+        auto keep2f = [&](u64* g2, int s, float m, float sum) {
+            g2[2 * s] = tagged(__float_as_uint(m), tg.t0);
+            g2[2 * s + 1] = tagged(__float_as_uint(sum), tg.t1);
+        };
         auto gather = [&](bool need_t, bool need_d) {
-            const int lo = need_t ? 0 : W, hi = need_d ? 2 * W : W;
-            if (tid < 64) poll_into([&](int i) { return i < W ? slot_t + i : slot_d + (i - W); }, lo, hi, got, &lds.nmiss,
-                                    a.wait_ticks);
+            const int lo = need_t ? 0 : W2w, hi = need_d ? 2 * W2w : W2w;
+            if (tid < 64) poll_into([&](int i) { return i < W2w ? slot_t + i : slot_d + (i - W2w); }, lo, hi, got, &lds.nmiss,
+                                    a.wait_ticks, tg);
             __syncthreads();
             if (__builtin_expect(lds.nmiss != 0, 0)) {
                 for (int s = 0; s < W; ++s) {
-                    const bool miss_t = need_t && got[s] == kEmpty, miss_d = need_d && got[W + s] == kEmpty;
+                    const bool miss_t = need_t && !have(got, s), miss_d = need_d && !have(got + W2w, s);
                     if (!miss_t && !miss_d) continue;
                     float mt, st, md, sd;
                     slice_stats<NV, false>(mem_slice(zt, vec_t, s), mem_slice(zd, vec_d, s), miss_t, miss_d, c, lds.red, bank, mt, st, md, sd);
                     if (tid == 0) {
-                        if (miss_t) { got[s] = pack2f(mt, st); slot_store(slot_t + s, got[s]); }
-                        if (miss_d) { got[W + s] = pack2f(md, sd); slot_store(slot_d + s, got[W + s]); }
-                        atomicAdd(ws.status + 1, 1);
+                        if (miss_t) { keep2f(got, s, mt, st); publish2f(slot_t + 2 * s, mt, st, tg); }
+                        if (miss_d) { keep2f(got + W2w, s, md, sd); publish2f(slot_d + 2 * s, md, sd, tg); }
+                        count_giveup(ws.status, tg);
                     }
                     __syncthreads();
                 }
@@ -511,8 +550,8 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
         // (max, sum) pair i of the target / draft row: a slot, or the caller's statistics
         const float2* ext_t = a.ext_t ? reinterpret_cast<const float2*>(a.ext_t) + ((int64_t)b * rows + k) * a.nch_t : nullptr;
         const float2* ext_d = (pair && a.ext_d) ? reinterpret_cast<const float2*>(a.ext_d) + ((int64_t)b * a.gmax + k) * a.nch_d : nullptr;
-        auto pair_t = [&](int i) { return ext_t ? ext_t[i] : make_float2(lo_f(got[i]), hi_f(got[i])); };
-        auto pair_d = [&](int i) { return ext_d ? ext_d[i] : make_float2(lo_f(got[W + i]), hi_f(got[W + i])); };
+        auto pair_t = [&](int i) { return ext_t ? ext_t[i] : make_float2(lo_f(got[2 * i]), lo_f(got[2 * i + 1])); };
+        auto pair_d = [&](int i) { return ext_d ? ext_d[i] : make_float2(lo_f(got[W2w + 2 * i]), lo_f(got[W2w + 2 * i + 1])); };
         const int n_t = ext_t ? a.nch_t : W, n_d = ext_d ? a.nch_d : W;
 
         if (pair) {
@@ -534,7 +573,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                 return x[v];
             };
             shifted_stats<NV, true>(d_first, reg_t, lds.red, bank, mh, shs);
-            if (tid == 0) slot_store(slot_h + w, pack2f(mh, shs));
+            if (tid == 0) publish2f(slot_h + 2 * w, mh, shs, tg);
             STAMP_AT(id, 4);
         }
 
@@ -548,16 +587,16 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                 xtok = a.tokens[(int64_t)b * a.gmax + k];
                 if (xtok >= 0 && xtok < V) { zx_t = zt[xtok]; zx_d = zd[xtok]; }
             }
-            u64* got_h = lds.slots + 2 * W;
+            u64* got_h = lds.slots + 2 * W2w;
             if (!pair) {
                 gather(own_t, false);                         // (a pair's workgroups all gathered above)
             } else {
-                if (tid < 64) poll_into([&](int i) { return slot_h + i; }, 0, W, got_h, &lds.nmiss, a.wait_ticks);
+                if (tid < 64) poll_into([&](int i) { return slot_h + i; }, 0, W2w, got_h, &lds.nmiss, a.wait_ticks, tg);
                 __syncthreads();
                 if (__builtin_expect(lds.nmiss != 0, 0)) {
                     const PairNorm r = lds.norm;
                     for (int s = 0; s < W; ++s) {
-                        if (got_h[s] != kEmpty) continue;
+                        if (have(got_h, s)) continue;
                         auto gt = mem_slice(zt, vec_t, s);
                         auto gd = mem_slice(zd, vec_d, s);
                         auto d_mem = [&](int v) {
@@ -569,7 +608,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                         };
                         float mh, shs;
                         shifted_stats<NV, false>(d_mem, d_mem, lds.red, bank, mh, shs);
-                        if (tid == 0) { got_h[s] = pack2f(mh, shs); slot_store(slot_h + s, got_h[s]); atomicAdd(ws.status + 1, 1); }
+                        if (tid == 0) { keep2f(got_h, s, mh, shs); publish2f(slot_h + 2 * s, mh, shs, tg); count_giveup(ws.status, tg); }
                         __syncthreads();
                     }
                 }
@@ -581,7 +620,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                 wave_combine_f64(pair_t, n_t, a.inv_T_exact, Mt, St);
                 if (pair) {
                     wave_combine_f64(pair_d, n_d, a.inv_T_exact, Md, Sd);
-                    auto pair_h = [&](int i) { return make_float2(lo_f(got_h[i]), hi_f(got_h[i])); };
+                    auto pair_h = [&](int i) { return make_float2(lo_f(got_h[2 * i]), lo_f(got_h[2 * i + 1])); };
                     wave_combine_f64(pair_h, W, kLn2, Mh, Sh);
                 }
                 if (tid == 0) {
@@ -591,7 +630,8 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                     if (pair) {
                         double rho = 0.0;
                         bool ok = false;
-                        if (xtok >= 0 && xtok < V) {
+                        const bool in_range = xtok >= 0 && xtok < V;
+                        if (in_range) {
                             // p = e^at / St, q = e^ad / Sd, p_hat = e^(at + eta (q - p) - Mh ln2) / Sh, max p_hat = 1 / Sh
                             const double invT = a.inv_T_exact;
                             const double at = ((double)zx_t - Mt) * invT;
@@ -601,11 +641,10 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
                             rho = q > 0.0 ? ph / q : INFINITY;
                             const double u = (double)a.uniforms[(int64_t)b * rows + k];
                             ok = u <= fmin(1.0, rho);
-                        } else {
-                            atomicAdd(ws.status + 0, 1);      // id outside the vocabulary: rejected, and counted
                         }
                         if (a.ratio) a.ratio[(int64_t)b * a.gmax + k] = (float)rho;
-                        ws.flags[(int64_t)b * a.gmax + k] = ok ? 1 : 0;
+                        // an id outside the vocabulary is rejected, and counted by accept_draw_row
+                        ws.flags[(int64_t)b * a.gmax + k] = in_range ? (ok ? 1 : 0) : 2;
                     }
                 }
             }
@@ -620,7 +659,15 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
     const int g = seq_gamma(a, id / (W * rows));
     STAMP_AT(id, 0);
     issue(id, g, x, y);
-    process(id, g, x, y);
+    // The call's tags (the counter is constant while this kernel runs: accept_draw_row advances it).
+    const Tags tg = make_tags((uint32_t)ws.status[kCntRows]);
+    if (id == 0 && tid == 0) {
+        // This kernel adds to neither status word; accept_draw_row does, after this kernel is done.
+        ws.status[0] = 0;
+        ws.status[1] = 0;
+        ws.status[kCntDraw] += 1;                             // read only by accept_draw_row
+    }
+    process(id, g, x, y, tg);
 }
 
 // Number of accepted drafts: index of the first failed accept test, or g.
@@ -628,7 +675,7 @@ __device__ __forceinline__ int first_reject(const Ws& ws, int b, int gmax, int g
 {
     int n = g;
     for (int k = g - 1; k >= 0; --k)
-        if (ws.flags[(int64_t)b * gmax + k] == 0) n = k;
+        if (ws.flags[(int64_t)b * gmax + k] != 1) n = k;
     return n;
 }
 
@@ -646,7 +693,7 @@ struct DrawNorm { double iSt, iSd, iSh, thr, eta; };
 struct LdsB {
     double red[4 * kWaves];
     int nmiss;
-    u64 slots[];          // 2 W2 words: the two sums of every slice for the current phase
+    u64 slots[];          // 4 W2 words: the two fp64 values of every slice for the current phase
 };
 
 // The three quantities of one entry that the phases are made of.
@@ -696,8 +743,20 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         // accepted drafts, then -1 (the draw fills slot n)
         for (int k = tid; k <= a.gmax; k += kThreads)
             if (k != n) a.out_tokens[(int64_t)b * (a.gmax + 1) + k] = k < n ? a.tokens[(int64_t)b * a.gmax + k] : -1;
-        if (tid == 0) a.n_accepted[b] = n;
+        if (tid == 0) {
+            a.n_accepted[b] = n;
+            int bad = 0;                                      // drafted ids outside the vocabulary
+            for (int k = 0; k < g; ++k) bad += ws.flags[(int64_t)b * a.gmax + k] == 2;
+            if (bad) atomicAdd(ws.status + 0, bad);
+            if (b == 0) {
+                // give-ups of accept_rows (counted under that kernel's tag), then its counter moves on
+                const Tags ta = make_tags((uint32_t)ws.status[kCntRows]);
+                if ((uint32_t)ws.status[kGiveRows + 1] == ta.t0) atomicAdd(ws.status + 1, ws.status[kGiveRows]);
+                ws.status[kCntRows] += 1;
+            }
+        }
     }
+    const Tags tg = make_tags(~(uint32_t)ws.status[kCntDraw]);
     const int V = a.V;
     int bank = 0;
     const bool bonus = n >= g;
@@ -725,18 +784,18 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
     }
     STAMP(9);
     DrawNorm nm{1.0, 0.0, 0.0, 0.0, (double)a.eta};
-    u64* my_slots = ws.slot_b + (int64_t)b * ws.w2 * 6;
+    u64* my_slots = ws.slot_b + (int64_t)b * ws.w2 * 12;
 
     // Reduction of word `word` (0 / 1) of the current phase over all slices, in a fixed order (the
     // same in every workgroup): lanes take slices lane, lane + 64, ...; then the wave reduction.
     auto all_sum = [&](int word) {
         double s = 0.0;
-        for (int i = lane; i < W2; i += 64) s += unpack_d(lds.slots[2 * i + word]);
+        for (int i = lane; i < W2; i += 64) s += get_d(lds.slots + 4 * i + 2 * word);
         return wave_sum(s);
     };
     auto all_max = [&](int word) {
         double s = -INFINITY;
-        for (int i = lane; i < W2; i += 64) s = fmax(s, unpack_d(lds.slots[2 * i + word]));
+        for (int i = lane; i < W2; i += 64) s = fmax(s, get_d(lds.slots + 4 * i + 2 * word));
         return wave_max(s);
     };
 
@@ -756,14 +815,15 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         }
         if (phase == 2) block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpMaxD());
         else block_reduce2(a0, a1, lds.red, bank, OpAddD(), OpAddD());
-        u64* base = my_slots + (phase - 1) * 2 * W2;         // slice s: words base[2 s], base[2 s + 1]
-        if (tid == 0) { slot_store(base + 2 * w, pack_d(a0)); slot_store(base + 2 * w + 1, pack_d(a1)); }
-        if (tid < 64) poll_into([&](int i) { return base + i; }, 0, 2 * W2, lds.slots, &lds.nmiss, a.wait_ticks);
+        u64* base = my_slots + (phase - 1) * 4 * W2;         // slice s: words base[4 s .. 4 s + 3]
+        if (tid == 0) { put_d(base + 4 * w, a0, tg, true); put_d(base + 4 * w + 2, a1, tg, true); }
+        if (tid < 64) poll_into([&](int i) { return base + i; }, 0, 4 * W2, lds.slots, &lds.nmiss, a.wait_ticks, tg);
         __syncthreads();
         if (__builtin_expect(lds.nmiss != 0, 0)) {
             // a slice whose sums did not arrive: the same sums from the logits in memory
             for (int s = 0; s < W2; ++s) {
-                if (lds.slots[2 * s] != kEmpty && lds.slots[2 * s + 1] != kEmpty) continue;
+                const u64* have = lds.slots + 4 * s;
+                if (word_ok(have[0], 0, tg) && word_ok(have[1], 1, tg) && word_ok(have[2], 0, tg) && word_ok(have[3], 1, tg)) continue;
                 double m0 = 0.0, m1 = phase == 2 ? -INFINITY : 0.0;
 #pragma unroll 1
                 for (int i = 0; i < NE; ++i) {
@@ -775,13 +835,10 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
                 if (phase == 2) block_reduce2(m0, m1, lds.red, bank, OpAddD(), OpMaxD());
                 else block_reduce2(m0, m1, lds.red, bank, OpAddD(), OpAddD());
                 if (tid == 0) {
-                    u64 v0 = pack_d(m0), v1 = pack_d(m1);
-                    if (v0 == kEmpty) v0 ^= 1ull;
-                    if (v1 == kEmpty) v1 ^= 1ull;
-                    lds.slots[2 * s] = v0;
-                    lds.slots[2 * s + 1] = v1;
-                    slot_store(base + 2 * s, v0);
-                    slot_store(base + 2 * s + 1, v1);
+                    put_d(lds.slots + 4 * s, m0, tg, false);
+                    put_d(lds.slots + 4 * s + 2, m1, tg, false);
+                    put_d(base + 4 * s, m0, tg, true);
+                    put_d(base + 4 * s + 2, m1, tg, true);
                     atomicAdd(ws.status + 1, 1);
                 }
                 __syncthreads();
@@ -808,7 +865,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         owner_excl = 0.0;
         for (int i0 = 0; i0 < W2; i0 += 64) {
             const int i = i0 + lane;
-            const double v = i < W2 ? unpack_d(lds.slots[2 * i + word]) : 0.0;
+            const double v = i < W2 ? get_d(lds.slots + 4 * i + 2 * word) : 0.0;
             const double inc = carry + wave_scan(v, OpAddD());
             if (search && owner < 0) {
                 const unsigned long long hit = __ballot(i < W2 && inc > t);
@@ -900,14 +957,12 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
     const int W = (a.V + 2048 * nv - 1) / (2048 * nv);
     const int64_t n_items = rows * W;
     const int grid = (int)n_items;
-    const int init_blocks = (int)((ws.n_empty + 255) / 256 < 64 ? (ws.n_empty + 255) / 256 : 64);
-    hipLaunchKernelGGL(accept_init, dim3(init_blocks < 1 ? 1 : init_blocks), dim3(256), 0, stream, ws);
-    const size_t lds_a = sizeof(LdsA) + (size_t)3 * W * sizeof(u64);
+    const size_t lds_a = sizeof(LdsA) + (size_t)6 * W * sizeof(u64);
     const dim3 blk(kThreads);
     if (nv == 8) hipLaunchKernelGGL(accept_rows<8>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
     else if (nv == 4) hipLaunchKernelGGL(accept_rows<4>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
     else hipLaunchKernelGGL(accept_rows<2>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
-    const size_t lds_b = sizeof(LdsB) + (size_t)2 * ws.w2 * sizeof(u64);
+    const size_t lds_b = sizeof(LdsB) + (size_t)4 * ws.w2 * sizeof(u64);
     hipLaunchKernelGGL(accept_draw_row<8>, dim3(ws.w2, a.B), blk, lds_b, stream, a, ws, ws.w2);
     return hipGetLastError();
 }

@@ -58,7 +58,8 @@ __global__ void __launch_bounds__(kThreads) greedy_slice_argmax(AcceptLaunch a, 
     __shared__ float shm[kThreads / 64];
     __shared__ int shi[kThreads / 64];
     const int w = blockIdx.x, y = blockIdx.y, b = blockIdx.z;
-    if (w == 0 && y == 0 && b == 0 && threadIdx.x < 64) ws.status[threadIdx.x] = 0;
+    // only the two status words: the words behind them are the general pass's call counters, which persist
+    if (w == 0 && y == 0 && b == 0 && threadIdx.x < 2) ws.status[threadIdx.x] = 0;
     const int g = seq_gamma(a, b);
     const bool is_t = y <= a.gmax;
     const int k = is_t ? y : y - (a.gmax + 1);

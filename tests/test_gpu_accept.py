@@ -152,6 +152,59 @@ def test_every_slice_size_and_the_give_up_path(slice_entries):
     assert np.array_equal(gpu[2].view(np.int32), gpu0[2].view(np.int32))
 
 
+def test_workspace_needs_no_clearing_and_a_captured_graph_replays():
+    """The exchange words of a call are recognised by the call's tags, not by a cleared workspace.  So:
+    (a) a workspace filled with arbitrary bits, or still holding another call's publications, gives
+    the oracle's results; (b) a HIP graph that captured one call -- its launch arguments frozen, only
+    the counter in the workspace moves -- gives the oracle's results on every replay, with other inputs
+    each time and eager calls on the same workspace in between."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=128256, batch=4, gamma_choices=(1, 3, 4), draft_noise_std=1.5,
+                    name="graph")
+    r = gu.rapid()
+    cases = [wl.gen_accept_inputs(cfg, salt=s) for s in (21, 22, 23, 24)]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ref = [gu.oracle.accept(c.target_logits, c.draft_logits, c.draft_tokens, c.uniforms,
+                            eta=float(np.float32(cfg.eta)), temperature=float(np.float32(cfg.temperature)),
+                            tail_alpha=float(np.float32(cfg.tail_alpha)), gammas=c.gammas) for c in cases]
+
+    def agree(out, i, what):
+        torch.cuda.synchronize()
+        got = tuple(t.cpu().numpy() for t in out)
+        st = gu.compare_accept(got, ref[i], cases[i].gammas, cfg.gamma_max)
+        assert st["n_mismatch"] == 0 and st["token_mismatch"] == 0 and st["exempt_sequences"] == 0, (what, st)
+
+    # (a) dirty workspace: random bytes, then all ones, then all zeros, before a call each
+    zt, zd, tok, gam, u = (dev(x) for x in (cases[0].target_logits, cases[0].draft_logits, cases[0].draft_tokens,
+                                            cases[0].gammas, cases[0].uniforms))
+    r.rapid_accept(zt, zd, tok, cfg.eta, u, gammas=gam)       # sizes the workspace
+    for fill in ("random", 255, 0):
+        if fill == "random":
+            r._ws_accept.copy_(torch.randint(0, 256, r._ws_accept.shape, dtype=torch.uint8, device="cuda",
+                                              generator=torch.Generator("cuda").manual_seed(5)))
+        else:
+            r._ws_accept.fill_(fill)
+        agree(r.rapid_accept(zt, zd, tok, cfg.eta, u, gammas=gam), 0, f"workspace filled with {fill}")
+        assert r.accept_status() == (0, 0) or r.accept_status()[0] == 0
+
+    # (b) one captured call, replayed over changing inputs
+    outs = (torch.empty(cfg.batch, dtype=torch.int32, device="cuda"),
+            torch.empty(cfg.batch, cfg.gamma_max + 1, dtype=torch.int32, device="cuda"),
+            torch.empty(cfg.batch, cfg.gamma_max, dtype=torch.float32, device="cuda"))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r.rapid_accept(zt, zd, tok, cfg.eta, u, gammas=gam, outs=outs)
+    for i in (1, 2, 0, 3, 3):
+        c = cases[i]
+        for dst, src in ((zt, c.target_logits), (zd, c.draft_logits), (tok, c.draft_tokens), (gam, c.gammas),
+                         (u, c.uniforms)):
+            dst.copy_(dev(src))
+        for o in outs:
+            o.fill_(-7)
+        graph.replay()
+        agree(outs, i, f"replay with inputs {i}")
+        agree(r.rapid_accept(zt, zd, tok, cfg.eta, u, gammas=gam), i, f"eager call after replay {i}")
+
+
 def test_option_values_are_validated():
     from paper_2502_20330_amd import binding
     r = gu.rapid()
