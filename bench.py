@@ -116,14 +116,16 @@ def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
     tokens = int(seqs.ctx_lens.astype(np.int64).sum())
     shape = r.attn_shape(qs[0], ks[0], seqs.max_ctx, page_table=page_table, softmax_scale=cfg.softmax_scale,
                          ctx_sum_hint=tokens)
-    ws = torch.empty(max(lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape)),
-                         lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V), 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape)), 256),
+                     dtype=torch.uint8, device=dev)
+    # a workspace of its own: the accept pass keeps a call counter in it from one call to the next
+    ws_a = torch.empty(max(lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V), 256), dtype=torch.uint8, device=dev)
     stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     P = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
     attn_args = [(r._ctx, ctypes.byref(shape), P(qs[l]), P(ks[l]), P(vs[l]), P(ctx_lens), P(gammas), P(page_table),
                   P(out), None, P(ws), ws.numel(), stream) for l in range(nbuf)]
     acc_args = (r._ctx, B, gmax, V, P(zt), P(zd), P(draft_tokens), P(gammas), float(cfg.eta), float(cfg.temperature),
-                float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), None, P(ws), ws.numel(), stream)
+                float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), None, P(ws_a), ws_a.numel(), stream)
 
     def check(rc):
         if rc != 0:
@@ -158,6 +160,54 @@ def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
             "accept_us": round(acc_us, 2), "accept_logit_bytes": logit_bytes,
             "accept_gbps": round(logit_bytes / (acc_us * 1e-6) / 1e9, 1),
             "accept_frac_of_peak": round(logit_bytes / (acc_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+
+def accept_batches(r, cfg, batches=(1, 8, 64), iters=10):
+    """The accept pass of `cfg` (its vocabulary, gamma, eta, temperature) on batches of several sizes: time per
+    call and logit bytes per second.  The logits rotate over up to eight buffers so that no call finds them in
+    the Infinity Cache; every sequence has its drafter's own arg-max as drafted tokens."""
+    import torch
+
+    from paper_2502_20330_amd import workloads as wl
+    dev = r.device
+    lib = r.lib
+    gmax, V = cfg.gamma_max, cfg.vocab
+    out = {}
+    for B in batches:
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.SEED_LOGITS + B)
+        logit_bytes = B * (2 * gmax + 1) * V * 4
+        nbuf = max(1, min(8, (600 << 20) // logit_bytes))
+        bufs = []
+        for _ in range(nbuf):
+            zt = torch.randn((B, gmax + 1, V), device=dev, generator=g) * cfg.logit_std
+            zd = (zt[:, :gmax] + torch.randn((B, gmax, V), device=dev, generator=g) * (cfg.draft_noise_std or 1.0)).contiguous()
+            bufs.append((zt, zd, torch.argmax(zd, dim=-1).to(torch.int32)))
+        u = torch.rand((B, gmax + 1), device=dev, generator=g)
+        n_acc = torch.empty(B, dtype=torch.int32, device=dev)
+        out_tok = torch.empty((B, gmax + 1), dtype=torch.int32, device=dev)
+        ws = torch.empty(max(lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V), 256), dtype=torch.uint8, device=dev)
+        stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        P = lambda t: ctypes.c_void_p(t.data_ptr())
+        calls = [(r._ctx, B, gmax, V, P(zt), P(zd), P(tok), None, float(cfg.eta), float(cfg.temperature),
+                  float(cfg.tail_alpha), P(u), P(n_acc), P(out_tok), None, P(ws), ws.numel(), stream)
+                 for zt, zd, tok in bufs]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3 + iters):
+            if i == 3:
+                e0.record()
+            rc = lib.rapid_accept(*calls[i % nbuf])
+            if rc != 0:
+                raise RuntimeError(f"librapid status {rc}: {lib.rapid_strerror(rc).decode()}")
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / iters * 1e3
+        gbps = logit_bytes / (us * 1e-6) / 1e9
+        out[str(B)] = {"accept_us": round(us, 2), "logit_bytes": logit_bytes, "gbps": round(gbps, 1),
+                       "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        del bufs, calls
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -254,14 +304,15 @@ def main():
     chunk = r.verify_attn_chunk(shape)
     ws_attn = lib.rapid_verify_attn_workspace_bytes(r._ctx, ctypes.byref(shape))
     ws_acc = lib.rapid_accept_workspace_bytes(r._ctx, B, gmax, V)
-    ws = torch.empty(max(ws_attn, ws_acc, 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(ws_attn, 256), dtype=torch.uint8, device=dev)
+    ws_a = torch.empty(max(ws_acc, 256), dtype=torch.uint8, device=dev)      # the accept pass's own (it keeps state)
     stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     P = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
     attn_args = [(r._ctx, ctypes.byref(shape), P(qs[l]), P(ks[l]), P(vs[l]), P(ctx_lens), P(gammas), P(page_table),
                   P(outs[l & 1]), None, P(ws), ws.numel(), stream) for l in range(nbuf)]
     acc_args = (r._ctx, B, gmax, V, P(zt), P(zd), P(draft_tokens), P(gammas), float(cfg.eta),
                 float(cfg.temperature), float(cfg.tail_alpha), P(uniforms), P(n_acc), P(out_tok), P(ratio),
-                P(ws), ws.numel(), stream)
+                P(ws_a), ws_a.numel(), stream)
 
     if head:
         head_args = (r._ctx, B * (gmax + 1), cfg.hidden, V, P(head[0]), P(head[1]), float(cfg.temperature),
@@ -387,6 +438,7 @@ def main():
         torch.cuda.empty_cache()
         result["also"] = {name: also_workload(r, wl.CONFIGS[name], n_layers, head_major)
                           for name, n_layers in (("ragged_paged", 1), ("llama70b_128k_step", 8))}
+        result["also"]["accept_by_batch"] = accept_batches(r, cfg)
         also_mode = True
     else:
         also_mode = False

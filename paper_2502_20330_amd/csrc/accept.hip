@@ -224,7 +224,9 @@ __device__ __forceinline__ Tags make_tags(uint32_t counter)
 {
     return Tags{counter * 0x9E3779B1u + 0x7F4A7C15u, (counter * 0x85EBCA77u) ^ 0xC2B2AE3Du};
 }
-__device__ __forceinline__ bool word_ok(u64 v, int i, const Tags& t) { return (uint32_t)(v >> 32) == ((i & 1) ? t.t1 : t.t0); }
+// the tag of word i (by its parity), without indexing into the pair
+__device__ __forceinline__ uint32_t tag_of(int i, const Tags& t) { return t.t0 ^ ((t.t0 ^ t.t1) & (0u - (uint32_t)(i & 1))); }
+__device__ __forceinline__ bool word_ok(u64 v, int i, const Tags& t) { return (uint32_t)(v >> 32) == tag_of(i, t); }
 __device__ __forceinline__ u64 tagged(uint32_t payload, uint32_t tag) { return (u64)payload | ((u64)tag << 32); }
 __device__ __forceinline__ float lo_f(u64 v) { return __uint_as_float((uint32_t)v); }
 // Two floats = one slot of two words; p must be an even offset into its array.
@@ -290,6 +292,7 @@ __device__ __forceinline__ void poll_into(Addr addr, int lo, int hi, u64* dst, i
 {
     const int lane = threadIdx.x;
     const int64_t t0 = (int64_t)wall_clock64();
+    const uint32_t want = tag_of(lane, tg);               // every word of this lane has the lane's parity
     int miss = 0;
     for (int i0 = lo; i0 < hi; i0 += 128) {
         const int ia = i0 + lane, ib = ia + 64;
@@ -298,11 +301,11 @@ __device__ __forceinline__ void poll_into(Addr addr, int lo, int hi, u64* dst, i
         for (;;) {
             if (pa) {
                 va = slot_load(addr(ia));
-                pa = !word_ok(va, ia, tg);
+                pa = (uint32_t)(va >> 32) != want;
             }
             if (pb) {
                 vb = slot_load(addr(ib));
-                pb = !word_ok(vb, ib, tg);
+                pb = (uint32_t)(vb >> 32) != want;
             }
             if (!__any(pa || pb)) break;
             if ((int64_t)wall_clock64() - t0 >= wait_ticks) break;
