@@ -704,11 +704,12 @@ __device__ __forceinline__ double draw_f(double et, double ed, const DrawNorm& n
 {
     return et * exp_c(nm.eta * (ed * nm.iSd - et * nm.iSt));
 }
-__device__ __forceinline__ double draw_weight(double et, double ed, const DrawNorm& nm, double& p)
+// f = draw_f(et, ed, nm): the register path kept it from phase 2, the memory path forms it again (same bits).
+__device__ __forceinline__ double draw_weight(double et, double ed, double f, const DrawNorm& nm, double& p)
 {
     p = et * nm.iSt;
     const double q = ed * nm.iSd;
-    double ph = draw_f(et, ed, nm) * nm.iSh;
+    double ph = f * nm.iSh;
     if (ph < nm.thr) ph = p;
     return fmax(fmax(p - ph, p - q), 0.0);
 }
@@ -725,7 +726,7 @@ __device__ __forceinline__ void draw_accumulate(int phase, double et, double ed,
         a1 = fmax(a1, f);
     } else {
         double p;
-        a0 += draw_weight(et, ed, nm, p);
+        a0 += draw_weight(et, ed, draw_f(et, ed, nm), nm, p);
         a1 += p;
     }
 }
@@ -770,7 +771,8 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
     const double* rec = ws.rows + ((int64_t)b * (a.gmax + 1) + n) * 4;
     const double Mt = rec[0], Md = rec[1], invT = a.inv_T_exact;
 
-    // own slice: e_t, e_d of the thread's entries, kept in registers for all phases
+    // own slice: e_t, e_d of the thread's entries, kept in registers for all phases; wgt holds
+    // f = e_t exp(eta (q - p)) after phase 2 and the draw weight after phase 3
     double et[NE], ed[NE], wgt[NE];
     const int64_t first = (int64_t)w * kSlice + (int64_t)tid * NE;
 #pragma unroll
@@ -807,9 +809,13 @@ __global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, W
         double a0 = 0.0, a1 = phase == 2 ? -INFINITY : 0.0;
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
-            if (phase == 3) {                                 // the weights are kept for the token search
+            if (phase == 2) {                                 // f is kept for phase 3 (no second exponential)
+                wgt[i] = draw_f(et[i], ed[i], nm);
+                a0 += wgt[i];
+                a1 = fmax(a1, wgt[i]);
+            } else if (phase == 3) {                          // the weights are kept for the token search
                 double p;
-                wgt[i] = draw_weight(et[i], ed[i], nm, p);
+                wgt[i] = draw_weight(et[i], ed[i], wgt[i], nm, p);
                 a0 += wgt[i];
                 a1 += p;
             } else {

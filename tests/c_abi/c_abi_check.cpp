@@ -205,6 +205,28 @@ int main()
                same ? "ok" : (near ? "near-tie (exempt)" : "FAIL"));
         failures += !(same || near);
     }
+    // ---------------------------------------------------------------- status block at the head of the workspace
+    int32_t status[2] = {-1, -1};
+    HIP_OK(hipMemcpy(status, ws2, sizeof(status), hipMemcpyDeviceToHost));
+    printf("accept status after valid ids: bad ids %d -> %s\n", status[RAPID_ACCEPT_STATUS_BAD_IDS],
+           status[RAPID_ACCEPT_STATUS_BAD_IDS] == 0 ? "ok" : "FAIL");
+    failures += status[RAPID_ACCEPT_STATUS_BAD_IDS] != 0;
+    // the same call with the first drafted id of sequence 0 outside the vocabulary: counted, position rejected
+    // (same workspace again: it is left as the first call wrote it, which is what the header asks for)
+    if (gammas_h[0] > 0) {
+        std::vector<int32_t> tok_bad = tok;
+        tok_bad[0] = V + 7;
+        HIP_OK(hipMemcpy(dtok, tok_bad.data(), tok_bad.size() * 4, hipMemcpyHostToDevice));
+        RAPID_OK_(rapid_accept(ctx, B, gmax, V, dzt, dzd, dtok, dgam, eta, T, alpha, duni, dn, dtoks, dratio, ws2,
+                               ws2_bytes, nullptr));
+        HIP_OK(hipDeviceSynchronize());
+        HIP_OK(hipMemcpy(status, ws2, sizeof(status), hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(n_acc.data(), dn, B * 4, hipMemcpyDeviceToHost));
+        const bool ok = status[RAPID_ACCEPT_STATUS_BAD_IDS] == 1 && n_acc[0] == 0;
+        printf("accept status after one id outside the vocabulary: bad ids %d, n of that sequence %d -> %s\n",
+               status[RAPID_ACCEPT_STATUS_BAD_IDS], n_acc[0], ok ? "ok" : "FAIL");
+        failures += !ok;
+    }
     rapid_destroy(ctx);
     printf(failures ? "FAILED\n" : "PASSED\n");
     return failures ? 1 : 0;
