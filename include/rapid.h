@@ -231,8 +231,9 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* Vocabulary entries per statistics chunk of rapid_lm_head for this device, vocabulary and row count (a
- * multiple of 16, at most 512 / ceil(n_rows / 16): one chunk per workgroup, sized so that the grid fills
- * the chip in whole rounds), and the number of chunks per row, ceil(vocab / chunk).  0 on bad sizes. */
+ * multiple of 16, at most 512: one chunk per workgroup, sized so that the grid fills the chip in whole
+ * rounds; it may depend on the row count), and the number of chunks per row, ceil(vocab / chunk).
+ * 0 on bad sizes. */
 int rapid_lm_head_chunk(const rapid_ctx* ctx, int vocab, int n_rows);
 int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab, int n_rows);
 

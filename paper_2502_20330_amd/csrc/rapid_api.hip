@@ -378,12 +378,10 @@ int rapid_accept(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
 }
 
 // Vocabulary rows per workgroup of the output head: the grid should fill the chip in whole
-// rounds (one workgroup per compute unit and round), with at most 512 / (blocks of 16 h rows) rows
-// per workgroup.
-static int lm_head_blocks(const rapid_ctx* ctx, int vocab, int n_rows)
+// rounds (one workgroup per compute unit and round), with at most 512 rows per workgroup.
+static int lm_head_blocks(const rapid_ctx* ctx, int vocab, int /*n_rows*/)
 {
-    const int nr = n_rows < 1 ? 1 : (n_rows + 15) / 16;
-    const int64_t nbmax = 32 / (nr > 6 ? 6 : nr);
+    const int64_t nbmax = 32;
     const int64_t blocks = ((int64_t)vocab + 15) / 16;
     const int64_t n_cu = ctx ? ctx->n_cu : 256;
     const int64_t rounds = (blocks + nbmax * n_cu - 1) / (nbmax * n_cu);
