@@ -86,17 +86,24 @@ def test_temperature_in_statistics(T):
     run(4, 1024, 2000, T=T, what=f"T{T}")
 
 
-def test_strided_logits_rows_and_no_stats():
-    h, w = wl.gen_lm_head_inputs(3, 1024, 777, salt=3)
+@pytest.mark.parametrize("rows,vocab,ldz,first", [(3, 777, 1000, 0), (3, 776, 1000, 0), (19, 776, 1001, 0),
+                                                  (3, 776, 1000, 1), (40, 2048, 2052, 2)])
+def test_strided_logits_rows_and_no_stats(rows, vocab, ldz, first):
+    """Row strides that are / are not a multiple of four floats and row starts that are / are not 16-byte
+    aligned (the kernel stores four logits at a time only where it may); nothing outside [0, vocab) of a
+    row is written."""
+    h, w = wl.gen_lm_head_inputs(rows, 1024, vocab, salt=3)
     hd, wd = gu.bf16_to_dev(h), gu.bf16_to_dev(w)
-    big = torch.full((3, 1000), 7.0, dtype=torch.float32, device="cuda")
-    view = big[:, :777]
+    big = torch.full((rows * ldz + 8,), 7.0, dtype=torch.float32, device="cuda")
+    view = big[first:first + rows * ldz].view(rows, ldz)[:, :vocab]
     gu.rapid().rapid_lm_head(hd, wd, want_stats=False, logits=view)
     torch.cuda.synchronize()
     ref = oracle.lm_head(h, w)
-    got = big.cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(got[:, :777] - ref) <= ATOL + RTOL * np.abs(ref))
-    assert np.all(got[:, 777:] == 7.0), "elements past the vocabulary must not be written"
+    flat = big.cpu().numpy().astype(np.float64)
+    got = flat[first:first + rows * ldz].reshape(rows, ldz)
+    assert np.all(np.abs(got[:, :vocab] - ref) <= ATOL + RTOL * np.abs(ref))
+    assert np.all(got[:, vocab:] == 7.0), "elements past the vocabulary must not be written"
+    assert np.all(flat[:first] == 7.0) and np.all(flat[first + rows * ldz:] == 7.0)
 
 
 def test_repeat_calls_are_bitwise_identical():
