@@ -284,8 +284,8 @@ int rapid_accept_prestats(rapid_ctx* ctx, int batch, int gamma_max, int vocab,
 
 /*
  * Cache bookkeeping around one validation round (implied by Alg. 1: the target scores
- * [C; x_<j] for every drafted position j, and "i <- j+1" per accepted draft, "i <- i+1"
- * after the residual draw).
+ * [C; x_<j] for every drafted position j; its index i advances to j+1 with every accepted
+ * draft and by one more after the residual draw).
  *
  * rapid_kv_append: row i (0 <= i <= gamma_b) of k_new / v_new becomes token
  * ctx_lens[b] - (gamma_b+1) + i of sequence b's cache; ctx_lens already counts the

@@ -45,8 +45,8 @@
  *       around a validation round: the keys/values of the gamma+1 verification
  *       positions become the last gamma+1 tokens of the cache before the target
  *       runs; after n drafts are accepted the sequence has grown by n+1 tokens
- *       (Alg. 1: "i <- j+1" per accepted draft, "i <- i+1" after the residual
- *       draw), of which the last has no key/value yet, so the cache keeps the
+ *       (Alg. 1: the index i moves to j+1 with every accepted draft and by one
+ *       more after the residual draw), of which the last has no key/value yet, so the cache keeps the
  *       first 1+n verification positions.
  *
  *   oracle_retrieve     -- chunk selection of the RAG drafter (Sec. 2.2; "RAG
