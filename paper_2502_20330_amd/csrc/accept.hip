@@ -731,8 +731,11 @@ __device__ __forceinline__ void draw_accumulate(int phase, double et, double ed,
     }
 }
 
-template <int NE>
-__global__ void __launch_bounds__(kThreads, 4) accept_draw_row(AcceptLaunch a, Ws ws, int W2)
+// OCC = waves per SIMD the kernel is compiled for: 4 (two workgroups per compute unit, 128 registers,
+// a few spilled) for grids of several rounds, 2 (256 registers, no spills) when every workgroup has a
+// compute unit to itself anyway.
+template <int NE, int OCC>
+__global__ void __launch_bounds__(kThreads, OCC) accept_draw_row(AcceptLaunch a, Ws ws, int W2)
 {
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
     LdsB& lds = *reinterpret_cast<LdsB*>(smem_raw);
@@ -972,6 +975,9 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t stream)
     else if (nv == 4) hipLaunchKernelGGL(accept_rows<4>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
     else hipLaunchKernelGGL(accept_rows<2>, dim3(grid), blk, lds_a, stream, a, ws, W, (int)n_items);
     const size_t lds_b = sizeof(LdsB) + (size_t)4 * ws.w2 * sizeof(u64);
-    hipLaunchKernelGGL(accept_draw_row<8>, dim3(ws.w2, a.B), blk, lds_b, stream, a, ws, ws.w2);
+    if ((int64_t)ws.w2 * a.B <= a.n_cu)
+        hipLaunchKernelGGL((accept_draw_row<8, 2>), dim3(ws.w2, a.B), blk, lds_b, stream, a, ws, ws.w2);
+    else
+        hipLaunchKernelGGL((accept_draw_row<8, 4>), dim3(ws.w2, a.B), blk, lds_b, stream, a, ws, ws.w2);
     return hipGetLastError();
 }
