@@ -673,13 +673,20 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
     process(id, g, x, y, tg);
 }
 
-// Number of accepted drafts: index of the first failed accept test, or g.
+// Number of accepted drafts: index of the first failed accept test, or g.  Every wave reads the flags of
+// all gmax positions, one per lane, without waiting for the sequence's own count g (one dependent memory
+// round trip less); positions >= g hold whatever an earlier call left and are cut off by the min.
 __device__ __forceinline__ int first_reject(const Ws& ws, int b, int gmax, int g)
 {
-    int n = g;
-    for (int k = g - 1; k >= 0; --k)
-        if (ws.flags[(int64_t)b * gmax + k] != 1) n = k;
-    return n;
+    const int lane = threadIdx.x & 63;
+    int n = 0x7fffffff;
+    for (int k0 = 0; k0 < gmax; k0 += 64) {
+        const int k = k0 + lane;
+        const int f = k < gmax ? ws.flags[(int64_t)b * gmax + k] : 1;
+        const unsigned long long rejected = __ballot(f != 1);
+        if (rejected && n == 0x7fffffff) n = k0 + __ffsll((long long)rejected) - 1;
+    }
+    return min(n, g);
 }
 
 // ---------------------------------------------------------------- accept_draw_row (fp64)
