@@ -66,7 +66,7 @@ def profile_traffic(kernel_key: str):
     return None
 
 
-def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
+def also_workload(r, cfg, n_layers, head_major, steps=5, warmup=2):
     """A short measurement of another workload (`n_layers` of its attention layers over rotating caches of at
     least 1 GiB, and its accept pass): per-layer attention time, effective KV GB/s, fraction of peak."""
     import numpy as np
@@ -131,9 +131,11 @@ def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
         if rc != 0:
             raise RuntimeError(f"librapid status {rc}: {lib.rapid_strerror(rc).decode()}")
 
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    attn_ms = acc_ms = 0.0
-    for it in range(warmup + steps):
+    # As in the main measurement, all steps are enqueued back to back and the host waits once at the end, so
+    # that no step starts on an idle device.  These workloads have short steps (0.4-0.8 ms), and the device needs
+    # several milliseconds of load before its clocks settle: the step count is therefore chosen by time, about
+    # 20 ms of untimed steps and at least 10 ms of timed ones, from the duration of a first step.
+    def one_step(it, e):
         first = (it * n_layers) % nbuf
         e[0].record()
         for a in attn_args[first:first + n_layers]:
@@ -141,10 +143,19 @@ def also_workload(r, cfg, n_layers, head_major, steps=3, warmup=1):
         e[1].record()
         check(lib.rapid_accept(*acc_args))
         e[2].record()
-        torch.cuda.synchronize()
-        if it >= warmup:
-            attn_ms += e[0].elapsed_time(e[1])
-            acc_ms += e[1].elapsed_time(e[2])
+
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    one_step(0, e)
+    torch.cuda.synchronize()
+    first_ms = max(e[0].elapsed_time(e[2]), 1e-3)
+    warmup = max(warmup, min(200, int(20.0 / first_ms) + 1))
+    steps = max(steps, min(100, int(10.0 / first_ms) + 1))
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(warmup + steps)]
+    for it in range(warmup + steps):
+        one_step(it + 1, evs[it])
+    torch.cuda.synchronize()
+    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs[warmup:])
+    acc_ms = sum(e[1].elapsed_time(e[2]) for e in evs[warmup:])
     per_layer_us = attn_ms / (steps * n_layers) * 1e3
     kv_bytes_layer = tokens * cfg.kv_bytes_per_token()
     gbps = kv_bytes_layer / (per_layer_us * 1e-6) / 1e9
