@@ -295,6 +295,28 @@ def test_paper_settings_gamma_10_llama_vocab(eta, T):
     check(cfg, acc, f"gamma=10 eta={eta} T={T}", eta=eta, temperature=T)
 
 
+@pytest.mark.parametrize("V,batch,gch,T", [(300000, 3, (2, 3), 1.0), (1 << 22, 2, (1, 2), 1.0), ((1 << 22) - 5, 1, (1,), 0.0),
+                                          (600001, 2, (3,), 0.0)])
+def test_vocabularies_of_more_than_64_slices(V, batch, gch, T):
+    """More than 64 slices per row (up to the largest vocabulary the header allows, 2^22): the loops that walk
+    the slices of a row 64 at a time -- polls, combines, the prefix over slice totals with its carry -- run
+    more than once; also in the greedy limit."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=V, batch=batch, gamma_choices=gch, draft_noise_std=1.0, logit_std=4.0,
+                    temperature=T if T > 0 else 1.0, name=f"V{V}")
+    acc = wl.gen_accept_inputs(cfg, salt=V % 97)
+    check(cfg, acc, f"V={V} T={T}", temperature=T)
+
+
+def test_more_than_64_drafted_positions():
+    """gamma = 70 (one kv-head group of one query head allows up to 95): the per-lane read of the accept flags
+    and the row loops run over more than one wave's worth of positions; rejects placed late so that n > 64 occurs."""
+    cfg = wl.scaled(wl.CONFIGS["tiny"], vocab=4099, batch=6, gamma_choices=(70, 66, 3), draft_noise_std=0.05,
+                    name="gamma70")
+    acc = wl.gen_accept_inputs(cfg, salt=5)
+    gpu, ref, _ = check(cfg, acc, "gamma=70", eta=0.5)
+    assert ref.n_accepted.max() > 64
+
+
 def test_nan_and_inf_logits_do_not_hang_or_write_out_of_range():
     """Behaviour on NaN / infinite logits is unspecified, but every call must return and every emitted
     token must be a vocabulary index or -1."""
