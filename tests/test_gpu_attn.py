@@ -276,6 +276,61 @@ def test_paper_setting_gamma_10_group_8_at_128k_full_size(head_major):
     check(cfg, wl.gen_attn_inputs(cfg, layer=1), what=f"{cfg.name}[head_major={head_major}]", head_major=head_major)
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_caches_beyond_4_gib(paged):
+    """A cache allocation of 5.4 GB per tensor: sequence and page bases lie past 2^32 bytes, so every base has
+    to be formed in 64 bits (only offsets inside one sequence or page may be 32-bit).  The sequences themselves
+    are short, so the host fills and the oracle reads only the tokens in use: contiguous, 40 sequences with
+    room for 131072 tokens each; paged, a pool of 163840 pages of 16 tokens of which the table uses the last ones."""
+    rng = np.random.default_rng(77)
+    B, Hq, Hkv, d, Q = 40, 8, 4, 128, 3
+    lens = rng.integers(300, 1000, size=B).astype(np.int32)
+    lens[-1] = 999
+    cap = 131072
+    tok = Hkv * d
+    n_used = 1008                                             # tokens per sequence that exist on the host
+    kh = wl._normal_bf16(rng, (B, n_used, Hkv, d))
+    vh = wl._normal_bf16(rng, (B, n_used, Hkv, d))
+    qh = wl._normal_bf16(rng, (B, Q, Hq, d))
+    q = gu.bf16_to_dev(qh)
+    ctx = torch.from_numpy(lens).cuda()
+    if not paged:
+        k = torch.empty((B, cap, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        assert k.numel() * 2 > (1 << 32)
+        k[:, :n_used] = gu.bf16_to_dev(kh)
+        v[:, :n_used] = gu.bf16_to_dev(vh)
+        out = gu.rapid().rapid_verify_attn(q, k, v, ctx, gamma=Q - 1, max_ctx=n_used, softmax_scale=0.2)
+        pt_host = None
+        lay = gu.oracle.KVLayout(n_used * tok, tok, d, 0, 0, 0)
+        kk, vv = kh, vh
+    else:
+        page, n_pages = 16, B * cap // 16
+        per_seq = n_used // page                              # 63 pages per sequence
+        k = torch.empty((n_pages, page, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        # sequence b uses the pages n_pages - 1 - (b * per_seq + j): the top of the pool, bases past 4 GiB
+        pt_host = (n_pages - 1 - (np.arange(B)[:, None] * per_seq + np.arange(per_seq)[None, :])).astype(np.int32)
+        assert int(pt_host.min()) * page * tok * 2 > (1 << 32)
+        idx = torch.from_numpy(pt_host.reshape(-1).astype(np.int64)).cuda()
+        k[idx] = gu.bf16_to_dev(kh).reshape(B * per_seq, page, Hkv, d)
+        v[idx] = gu.bf16_to_dev(vh).reshape(B * per_seq, page, Hkv, d)
+        out = gu.rapid().rapid_verify_attn(q, k, v, ctx, gamma=Q - 1, page_table=torch.from_numpy(pt_host).cuda(),
+                                           max_ctx=n_used, softmax_scale=0.2)
+        # the oracle sees a compact pool holding the same pages in table order
+        kk = kh.reshape(B * per_seq, page, Hkv, d)
+        vv = vh.reshape(B * per_seq, page, Hkv, d)
+        pt_compact = np.arange(B * per_seq, dtype=np.int32).reshape(B, per_seq)
+        lay = gu.oracle.KVLayout(0, tok, d, page, page * tok, per_seq)
+    torch.cuda.synchronize()
+    ref = gu.oracle.verify_attn(qh, kk, vv, lens, lay, Hkv=Hkv, scale=0.2, gammas=None,
+                             page_table=None if not paged else pt_compact, gamma=Q - 1)
+    ref = ref[0] if isinstance(ref, tuple) else ref
+    gu.assert_attn_close(gu.bf16_to_host(out), ref, what=f"cache beyond 4 GiB, paged={paged}")
+    del k, v
+    torch.cuda.empty_cache()
+
+
 def test_hbm_read_probe_runs_and_checks_arguments():
     """The measurement aid streams a buffer without touching it and rejects sizes it cannot split."""
     from paper_2502_20330_amd import binding
