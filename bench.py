@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import ctypes
+import hashlib
 import json
 import math
 import os
@@ -51,18 +52,31 @@ def parse_args():
     return ap.parse_args()
 
 
+TRAFFIC_SOURCES = {"verify_attn": "verify_attn.hip", "rapid_accept": "accept.hip", "rapid_lm_head": "lm_head.hip"}
+
+
+def source_sha256(kernel_key: str) -> str:
+    """Hash of the kernel source a traffic figure belongs to."""
+    path = os.path.join(ROOT, "paper_2502_20330_amd", "csrc", TRAFFIC_SOURCES[kernel_key])
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+
+
 def profile_traffic(kernel_key: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
-    summary (profiles/*.txt, a line `traffic_bytes_per_launch[<key>]: N`), or None."""
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary (profiles/*.txt, a line
+    `traffic_bytes_per_launch[<key>]: N`), or None.  The summary also records the hash of the kernel source
+    it was taken with (`source_sha256[<key>]: H`); a figure whose source has changed since is stale and is
+    not reported."""
     pdir = os.path.join(ROOT, "profiles")
     if not os.path.isdir(pdir):
         return None
     pat = re.compile(r"traffic_bytes_per_launch\[" + re.escape(kernel_key) + r"\]:\s*([0-9.eE+]+)")
+    hpat = re.compile(r"source_sha256\[" + re.escape(kernel_key) + r"\]:\s*([0-9a-f]+)")
     for name in sorted(os.listdir(pdir)):
         if name.endswith((".txt", ".md")):
-            m = pat.search(open(os.path.join(pdir, name)).read())
+            text = open(os.path.join(pdir, name)).read()
+            m, h = pat.search(text), hpat.search(text)
             if m:
-                return float(m.group(1))
+                return float(m.group(1)) if h and h.group(1) == source_sha256(kernel_key) else None
     return None
 
 
