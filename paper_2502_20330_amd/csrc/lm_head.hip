@@ -273,12 +273,15 @@ hipError_t configure_lm_head()
     if ((e = configure_one<128, 3>()) != hipSuccess) return e;
     if ((e = configure_one<128, 4>()) != hipSuccess) return e;
     if ((e = configure_one<128, 5>()) != hipSuccess) return e;
-    return configure_one<128, 6>();
+    if ((e = configure_one<128, 6>()) != hipSuccess) return e;
+    if ((e = configure_one<256, 3>()) != hipSuccess) return e;
+    if ((e = configure_one<256, 4>()) != hipSuccess) return e;
+    if ((e = configure_one<256, 5>()) != hipSuccess) return e;
+    return configure_one<256, 6>();
 }
 
-// Row blocks of 16 rows of h; one and two blocks use the 256-wide slab when the hidden size allows,
-// more blocks always the 128-wide one (the h operands of a slab must fit the register file next to
-// the accumulators).
+// Row blocks of 16 rows of h; the 256-wide slab when the hidden size allows (at six row blocks its h
+// operands and the accumulators take 384 of the 512 registers), else the 128-wide one.
 hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
 {
     const int nwg = (a.vocab + a.nb * 16 - 1) / (a.nb * 16);
@@ -288,10 +291,10 @@ hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
     switch (nr) {
         case 1: wide_slab ? launch_one<256, 1>(a, nwg, stream) : launch_one<128, 1>(a, nwg, stream); break;
         case 2: wide_slab ? launch_one<256, 2>(a, nwg, stream) : launch_one<128, 2>(a, nwg, stream); break;
-        case 3: launch_one<128, 3>(a, nwg, stream); break;
-        case 4: launch_one<128, 4>(a, nwg, stream); break;
-        case 5: launch_one<128, 5>(a, nwg, stream); break;
-        default: launch_one<128, 6>(a, nwg, stream); break;
+        case 3: wide_slab ? launch_one<256, 3>(a, nwg, stream) : launch_one<128, 3>(a, nwg, stream); break;
+        case 4: wide_slab ? launch_one<256, 4>(a, nwg, stream) : launch_one<128, 4>(a, nwg, stream); break;
+        case 5: wide_slab ? launch_one<256, 5>(a, nwg, stream) : launch_one<128, 5>(a, nwg, stream); break;
+        default: wide_slab ? launch_one<256, 6>(a, nwg, stream) : launch_one<128, 6>(a, nwg, stream); break;
     }
     return hipGetLastError();
 }
