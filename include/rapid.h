@@ -248,7 +248,7 @@ int rapid_lm_head_stat_chunks(const rapid_ctx* ctx, int vocab, int n_rows);
  * which is what rapid_accept_prestats consumes (the pieces of softmax(z/T), Alg. 1).
  *
  *   n_rows       1..96 (the gamma+1 rows of one sequence or of a batch, ordered [sequence][position])
- *   hidden       a multiple of 512 (multiples of 1024 take the faster path)
+ *   hidden       a multiple of 128 (multiples of 256 take the faster path)
  *   vocab        >= 16
  *   h            bf16 [n_rows, hidden], contiguous, 16-byte aligned
  *   w            bf16 [vocab, hidden], contiguous, 16-byte aligned

@@ -43,7 +43,7 @@ constexpr int kWaves = 4;
 constexpr int kNB = 32;                      // 16-row vocabulary blocks per workgroup
 constexpr int kRing = 32768;                 // LDS ring per wave
 // Tile geometry for a slab width of SK hidden elements (256, or 128 for hidden sizes
-// that are a multiple of 512 but not of 1024, e.g. 3584).
+// that are a multiple of 128 but not of 256).
 template <int SK>
 struct Tile {
     static constexpr int BYTES = 16 * SK * 2;          // 8 KiB / 4 KiB
@@ -286,8 +286,8 @@ hipError_t launch_lm_head(const LmHeadLaunch& a, hipStream_t stream)
 {
     const int nwg = (a.vocab + a.nb * 16 - 1) / (a.nb * 16);
     const int nr = (a.n_rows + 15) / 16;
-    if (a.hidden % 512 != 0 || nr < 1 || nr > 6 || a.nb < 1 || a.nb > kNB) return hipErrorInvalidValue;
-    const bool wide_slab = a.hidden % 1024 == 0;
+    if (a.hidden % 128 != 0 || nr < 1 || nr > 6 || a.nb < 1 || a.nb > kNB) return hipErrorInvalidValue;
+    const bool wide_slab = a.hidden % 256 == 0;
     switch (nr) {
         case 1: wide_slab ? launch_one<256, 1>(a, nwg, stream) : launch_one<128, 1>(a, nwg, stream); break;
         case 2: wide_slab ? launch_one<256, 2>(a, nwg, stream) : launch_one<128, 2>(a, nwg, stream); break;

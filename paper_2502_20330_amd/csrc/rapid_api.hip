@@ -409,7 +409,7 @@ int rapid_lm_head(rapid_ctx* ctx, int n_rows, int hidden, int vocab,
 {
     if (!ctx || !h || !w || !logits) return RAPID_EINVAL;
     if (n_rows < 1 || hidden < 1 || vocab < 1 || logits_row_stride < vocab || !(temperature > 0.f)) return RAPID_EINVAL;
-    if (n_rows > 96 || hidden % 512 || vocab < 16) return RAPID_EUNSUPPORTED;
+    if (n_rows > 96 || hidden % 128 || vocab < 16) return RAPID_EUNSUPPORTED;
     if (!aligned(h, 16) || !aligned(w, 16) || !aligned(logits, 4) || !aligned(stats, 8)) return RAPID_EALIGN;
     LmHeadLaunch a{};
     a.h = static_cast<const uint16_t*>(h);

@@ -76,7 +76,7 @@ def test_many_rows_on_other_widths_and_vocabulary_edges(rows, hidden, vocab):
     run(rows, hidden, vocab, salt=rows + hidden, what=f"rows{rows}_hidden{hidden}_vocab{vocab}")
 
 
-@pytest.mark.parametrize("hidden", [512, 1024, 1536, 3072, 3584, 4096, 5120, 8192])
+@pytest.mark.parametrize("hidden", [128, 256, 384, 512, 1024, 1408, 1536, 2304, 3072, 3584, 4096, 5120, 8192])
 def test_hidden_sizes(hidden):
     run(9, hidden, 2500, salt=hidden, what=f"hidden{hidden}")
 
@@ -125,7 +125,7 @@ def test_bad_arguments_return_error_codes():
     assert e.value.status == binding.RAPID_EUNSUPPORTED                      # 97 rows
     with pytest.raises(binding.RapidError) as e:
         r.rapid_lm_head(h[:4, :1000].contiguous(), w[:, :1000].contiguous())
-    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # hidden not a multiple of 512
+    assert e.value.status == binding.RAPID_EUNSUPPORTED                      # hidden not a multiple of 128
     with pytest.raises(binding.RapidError) as e:
         r.rapid_lm_head(h[:4], w, temperature=0.0)
     assert e.value.status == binding.RAPID_EINVAL
