@@ -82,7 +82,7 @@ def test_random_accept_case(c):
 
 def _head_cases(n=14):
     rng = np.random.default_rng(99)
-    return [dict(i=i, rows=int(rng.integers(1, 17)) if i % 3 else int(rng.integers(17, 97)), hidden=int(rng.choice([512, 1024, 1536, 2048, 2560, 4096])),
+    return [dict(i=i, rows=int(rng.integers(1, 17)) if i % 3 else int(rng.integers(17, 97)), hidden=int(rng.choice([128, 384, 512, 640, 1024, 1536, 2048, 2304, 2560, 4096])),
                  vocab=int(rng.integers(16, 40000)), T=float(rng.choice([0.1, 1.0, 2.0]))) for i in range(n)]
 
 
