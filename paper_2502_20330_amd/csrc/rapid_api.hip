@@ -119,8 +119,8 @@ int plan_chunk(const rapid_ctx* ctx, const rapid_attn_shape* s)
 //    batches; when heads interleave inside a token row it costs 2.5 %, because the
 //    workgroups that share those rows no longer run side by side.
 //  * skew: with a single wave of workgroups (one per compute unit) the dies on odd
-//    dispatch slots finish 10..15 % later than the even ones.  Moving 1/16 of a split
-//    from each odd-slot workgroup to its even-slot pair partner evens that out
+//    dispatch slots finish 10..15 % later than the even ones.  Moving about a tenth of a
+//    split from each odd-slot workgroup to its even-slot pair partner evens that out
 //    (2..3 % on the whole call).  With several workgroups per compute unit the
 //    dispatcher balances by itself and the skew only hurts.
 // The skew is a multiple of 128 tokens so both partners keep whole tiles per wave.
@@ -129,7 +129,11 @@ void plan_layout(const rapid_ctx* ctx, AttnLaunch& a)
     a.rot = a.hstride > a.tstride && a.Hkv > 1;
     a.skew = 0;
     const int64_t wgs = (int64_t)a.B * a.Hkv * a.nsplit;
-    if (a.rot && a.Hkv % 2 == 0 && a.nsplit >= 2 && wgs <= ctx->n_cu) a.skew = a.chunk / 16 / 128 * 128;
+    // measured: 3/32 of the split for the one-team kernel (config 3: 88.2 us with 384 tokens, 89.5 with 256,
+    // 91.1 with none), 1/16 for the two-team kernel, which runs all waves through the same number of tiles
+    // (70B shape: 93-94 us with 256 tokens, 96.5 with 384)
+    if (a.rot && a.Hkv % 2 == 0 && a.nsplit >= 2 && wgs <= ctx->n_cu)
+        a.skew = a.wide ? a.chunk / 16 / 128 * 128 : (a.chunk * 3 / 32 + 64) / 128 * 128;
 }
 
 }  // namespace
