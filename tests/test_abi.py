@@ -53,6 +53,63 @@ def test_strerror_and_shape_checks_need_no_gpu():
     assert lib.rapid_accept_workspace_bytes(None, 0, 8, 128256) == 0
 
 
+def _shape(batch, q_max, hq, hkv, d, max_ctx, token_major=True, page=0, hint=0):
+    s = binding.AttnShape()
+    s.batch, s.q_max, s.n_q_heads, s.n_kv_heads, s.head_dim, s.max_ctx = batch, q_max, hq, hkv, d, max_ctx
+    s.gamma, s.softmax_scale = q_max - 1, d ** -0.5
+    if page:
+        s.page_size, s.max_pages = page, -(-max_ctx // page)
+        s.kv_page_stride, s.kv_token_stride, s.kv_head_stride = page * hkv * d, hkv * d, d
+    elif token_major:
+        s.kv_batch_stride, s.kv_token_stride, s.kv_head_stride = max_ctx * hkv * d, hkv * d, d
+    else:
+        s.kv_batch_stride, s.kv_token_stride, s.kv_head_stride = max_ctx * hkv * d, d, max_ctx * d
+    s.ctx_sum_hint = hint
+    return s
+
+
+def test_split_planning_on_the_named_workloads_needs_no_gpu():
+    """Host-side planning (no context: 256 compute units assumed): tokens per KV split for the benchmark shapes,
+    the row cap, the 32-bit span limits and the chunk of the output head."""
+    lib = binding.load_library()
+    chunk = lambda s: lib.rapid_verify_attn_chunk(None, ctypes.byref(s))
+    # one workgroup per compute unit for sequences of equal length: 8 kv heads x 32 splits
+    assert chunk(_shape(1, 9, 32, 8, 128, 131072)) == 4096                      # configs 3 and 5
+    assert chunk(_shape(1, 9, 64, 8, 128, 131072)) == 4096
+    assert chunk(_shape(1, 9, 32, 8, 128, 32768)) == 1024                       # config 2
+    assert chunk(_shape(1, 11, 28, 4, 128, 131072)) == 2048                     # 4 kv heads x 64 splits
+    assert chunk(_shape(1, 1, 32, 8, 128, 8192)) == 256                         # drafter decode: the minimum
+    assert chunk(_shape(1, 5, 4, 1, 64, 2048)) == 256
+    # a ragged batch whose total the caller knows is planned for two rounds of workgroups
+    ragged = chunk(_shape(8, 9, 32, 8, 128, 131072, page=16, hint=560858))
+    plain = chunk(_shape(8, 9, 32, 8, 128, 131072, page=16))
+    assert ragged % 128 == 0 and plain % 128 == 0 and ragged < plain
+    assert 8 * (560858 // ragged + 8) <= 2 * 256 + 8 * 8
+    # an explicit split is rounded up to whole tiles of 128 tokens
+    s = _shape(1, 9, 32, 8, 128, 131072)
+    s.chunk_tokens = 1000
+    assert chunk(s) == 1024
+    # rows per kv head: (gamma + 1) * group <= 96
+    assert chunk(_shape(1, 11, 64, 8, 128, 131072)) > 0                         # 88 rows
+    assert chunk(_shape(1, 12, 64, 8, 128, 131072)) == 4096                     # 96 rows
+    assert chunk(_shape(1, 13, 64, 8, 128, 131072)) == -3                       # 104 rows
+    # offsets inside one sequence (or page) are 32-bit: 2^21 tokens x 2 KiB per token do not fit
+    assert chunk(_shape(1, 9, 32, 8, 128, 1 << 21)) == -3
+    assert chunk(_shape(1, 9, 32, 8, 128, 1 << 21, token_major=False)) > 0     # 256 B per token do
+    assert chunk(_shape(1, 9, 32, 8, 128, 1 << 21, page=16)) > 0               # and pages are small
+    # the workspace grows with the number of splits and rows
+    ws = lambda s: lib.rapid_verify_attn_workspace_bytes(None, ctypes.byref(s))
+    assert ws(_shape(1, 9, 64, 8, 128, 131072)) > ws(_shape(1, 9, 32, 8, 128, 131072)) > 0
+    assert ws(_shape(2, 9, 32, 8, 128, 131072)) >= ws(_shape(1, 9, 32, 8, 128, 131072))
+    # output head: one chunk per workgroup, whole rounds of 256 workgroups, at most 512 entries, any row count
+    for vocab, want in ((128256, 512), (152064, 304), (32000, 128), (16, 16), (1000, 16)):
+        for rows in (1, 9, 72, 96):
+            ch = lib.rapid_lm_head_chunk(None, vocab, rows)
+            assert ch == want, (vocab, rows, ch)
+            assert lib.rapid_lm_head_stat_chunks(None, vocab, rows) == -(-vocab // ch)
+    assert lib.rapid_lm_head_chunk(None, 128256, 97) == 0 and lib.rapid_lm_head_chunk(None, 0, 9) == 0
+
+
 def test_product_path_has_no_cpu_fallback():
     """Without a GPU the binding refuses to construct instead of computing elsewhere."""
     import torch
