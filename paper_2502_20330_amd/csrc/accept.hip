@@ -436,6 +436,7 @@ __device__ __forceinline__ void wave_combine_f64(Pair pair, int n, double scale,
 }
 
 struct LdsA {
+    double dec[4];        // Mt, St, Md, Sd of the row in fp64 (deciding workgroup)
     float red[4 * kWaves];
     PairNorm norm;
     int nmiss;
@@ -451,7 +452,7 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
     LdsA& lds = *reinterpret_cast<LdsA*>(smem_raw);
     constexpr int kSlice = kThreads * 4 * NV;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = a.V, rows = a.gmax + 1;
     int bank = 0;
     const float c = a.inv_T * kLog2e, eta_l2 = a.eta * kLog2e;
@@ -594,6 +595,14 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
             if (!pair) {
                 gather(own_t, false);                         // (a pair's workgroups all gathered above)
             } else {
+                // while wave 0 waits for the shifted statistics, waves 1 and 2 combine the row's two
+                // normalisers in fp64 (their slices were gathered before the shift)
+                if (wave == 1 || wave == 2) {
+                    double M, S;
+                    if (wave == 1) wave_combine_f64(pair_t, n_t, a.inv_T_exact, M, S);
+                    else wave_combine_f64(pair_d, n_d, a.inv_T_exact, M, S);
+                    if (lane == 0) { lds.dec[2 * (wave - 1)] = M; lds.dec[2 * (wave - 1) + 1] = S; }
+                }
                 if (tid < 64) poll_into([&](int i) { return slot_h + i; }, 0, W2w, got_h, &lds.nmiss, a.wait_ticks, tg);
                 __syncthreads();
                 if (__builtin_expect(lds.nmiss != 0, 0)) {
@@ -620,11 +629,12 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
             if (tid < 64) {
                 // one wave: fp64 combine of the row's statistics and the accept test of its drafted token
                 double Mt, St, Md = 0, Sd = 1, Mh = 0, Sh = 1;
-                wave_combine_f64(pair_t, n_t, a.inv_T_exact, Mt, St);
                 if (pair) {
-                    wave_combine_f64(pair_d, n_d, a.inv_T_exact, Md, Sd);
+                    Mt = lds.dec[0]; St = lds.dec[1]; Md = lds.dec[2]; Sd = lds.dec[3];
                     auto pair_h = [&](int i) { return make_float2(lo_f(got_h[2 * i]), lo_f(got_h[2 * i + 1])); };
                     wave_combine_f64(pair_h, W, kLn2, Mh, Sh);
+                } else {
+                    wave_combine_f64(pair_t, n_t, a.inv_T_exact, Mt, St);
                 }
                 if (tid == 0) {
                     double* rec = ws.rows + ((int64_t)b * rows + k) * 4;
