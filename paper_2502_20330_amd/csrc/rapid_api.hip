@@ -36,14 +36,13 @@ int page_hi_of(const rapid_attn_shape* s) { return s->n_pages > 0 ? s->n_pages -
 constexpr int kWideFromBlocks = RAPID_WIDE_FROM;    // row blocks from which the two-team attention kernel is used
 
 // Row blocks of 16 packed query rows that the partials of a shape are laid out in.  Five and six
-// blocks run on the two-team kernel, which works in pairs of blocks.
+// blocks run on the two-team kernel (teams of 3 + 2 and 3 + 3 blocks).
 int attn_row_blocks(const rapid_attn_shape* s, int* wide)
 {
     const int G = s->n_q_heads / s->n_kv_heads;
     const int rb = (s->q_max * G + 15) / 16;
-    const bool w = rb >= kWideFromBlocks;
-    if (wide) *wide = w ? 1 : 0;
-    return w ? (rb + 1) / 2 * 2 : rb;
+    if (wide) *wide = (rb >= kWideFromBlocks && rb >= 4) ? 1 : 0;
+    return rb;
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }

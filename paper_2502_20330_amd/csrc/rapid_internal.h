@@ -27,7 +27,7 @@ struct AttnLaunch {
     float* part_ml;     // [B, Hkv, nsplit, RB*16, 2] (running max in log2 units, sum)
     int32_t B, Qmax, Hq, Hkv, G, D, gamma;
     int32_t max_ctx;    // host bound of ctx_lens
-    int32_t chunk, nsplit, RB;   // RB: 16-row blocks of the partials (wide: two teams of RB/2 blocks)
+    int32_t chunk, nsplit, RB;   // RB: 16-row blocks of the partials (wide: two teams of (RB + 1) / 2 and RB / 2 blocks)
     int32_t wide;       // 1: eight-wave kernel with two row teams
     int32_t rot;        // 1: dispatch slot x serves head (x + split) mod Hkv, 0: head x
     int32_t skew;       // tokens moved from the splits on odd dispatch slots to those on even ones

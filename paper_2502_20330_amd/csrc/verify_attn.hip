@@ -548,83 +548,52 @@ __device__ __forceinline__ void dma_half_tile(const RowAddr& ra, uint32_t slot, 
     }
 }
 
-template <int D, int RBT>
+template <int D, int RB0, int RB1>
 constexpr int attn_wide_lds_bytes()
 {
-    constexpr int tiles = kWaves * Geo<D>::WAVE_LDS + 2 * RBT * 16 * Geo<D>::ROWB;          // four rings + the Q block
-    constexpr int merge = (2 * 2 * RBT * 16 * (D + 4) + 2 * kWaves * RBT * 16 * 2) * 4;   // two teams' exchange buffers
+    constexpr int RBM = RB0 > RB1 ? RB0 : RB1;
+    constexpr int tiles = kWaves * Geo<D>::WAVE_LDS + (RB0 + RB1) * 16 * Geo<D>::ROWB;          // four rings + the Q block
+    constexpr int merge = (2 * (RB0 + RB1) * 16 * (D + 4) + 2 * kWaves * RBM * 16 * 2) * 4;   // two teams' exchange buffers
     return tiles > merge ? tiles : merge;
 }
 
-template <int D, int RBT, bool PAGED>
-__global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLaunch a)
+// What a wave of the wide kernel knows before its team's part begins.
+struct WideWave {
+    RowAddr addr;
+    char *kring, *vring, *qlds;
+    uint32_t kring_lds, vring_lds;
+    int b, hkv, split, L, Q, R, c0, c1, ntq, last_tok;
+    int lane, wave, team, pr;
+};
+
+// One team's share of the wide kernel: RBT row blocks starting at packed row `row0`, from the Q
+// fragments to the team's partial in LDS (obuf: [2][RBT * 16][D + 4] floats; mlbuf: [8 waves][MLS][2]).
+// Both teams execute the same sequence of workgroup barriers (two per tile, three afterwards), so the
+// two instantiations of a kernel with unequal teams may sit in the two arms of a wave-uniform branch.
+template <int D, int RBT, int MLS, bool PAGED>
+__device__ __forceinline__ void wide_team(const AttnLaunch& a, const WideWave& w, char* smem, int row0, float* obuf,
+                                          float* mlbuf, int64_t pbase)
 {
     using G = Geo<D>;
-    constexpr int RPT = RBT * 16;          // rows of one team
-    constexpr int RP = 2 * RPT;            // rows of the workgroup (= a.RB * 16)
+    constexpr int RPT = RBT * 16;          // rows of this team
     constexpr int kWait = G::NLD;          // own loads issued after the tile a wait is for (two half tiles)
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-
-    const int split = blockIdx.y, b = blockIdx.z;
-    const int hkv = a.rot ? (int)((blockIdx.x + split) % a.Hkv) : (int)blockIdx.x;
-    const int L = min(a.ctx_lens[b], a.max_ctx);
-    const int c0 = split_begin(a, split, hkv);
-    if (c0 >= L) return;
-    const int c1 = min(split_end(a, split, hkv), L);
-    const int Q = seq_queries(a, b);
-    const int R = Q * a.G;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int team = wave >> 2, pr = wave & 3;          // row team, token quarter
+    const int lane = w.lane, wave = w.wave, team = w.team, pr = w.pr;
     const int ln = lane & 15, lg = lane >> 4;
-
-    const int ntile = (c1 - c0 + kTile - 1) / kTile;
-    const int ntq = (ntile + kWaves - 1) / kWaves;                              // tiles per quarter (uniform)
-    const int last_tok = min(c1, c0 + (pr + 1) * ntq * kTile) - 1;
+    const int L = w.L, Q = w.Q, R = w.R, c0 = w.c0, c1 = w.c1, ntq = w.ntq, last_tok = w.last_tok;
     auto tile_t0 = [&](int it) { return c0 + (pr * ntq + it) * kTile; };
-    const RowAddr addr = make_row_addr<PAGED>(a, b, hkv);
-    char* kring = smem + pr * G::WAVE_LDS;
-    char* vring = kring + 2 * G::SLOT;
-    const uint32_t kring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + pr * G::WAVE_LDS;
-    const uint32_t vring_lds = kring_lds + 2 * G::SLOT;
-
-    // Q block: RP rows, HBM -> LDS once per workgroup, the eight waves sharing the loads; issued
-    // before the first tiles so that it is complete when only tile loads are outstanding.
-    char* qlds = smem + kWaves * G::WAVE_LDS;
-    {
-        const uint32_t q_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + kWaves * G::WAVE_LDS;
-        constexpr int QI = RP / G::RPI;
-        const int last_row = a.Qmax * a.G - 1;
-        for (int e = wave; e < QI; e += 2 * kWaves) {
-            const int row = e * G::RPI + lane / G::CPR;
-            const int rr = min(row, last_row);
-            const int qi = rr / a.G, qg = rr % a.G;
-            const int c = (lane % G::CPR) ^ k_swz<D>(row);
-            const uint32_t off = (uint32_t)(((((int64_t)b * a.Qmax + qi) * a.Hq + hkv * a.G + qg) * D) * 2) + c * 16;
-            dma16_keep(reinterpret_cast<const char*>(a.q), off, q_lds + e * 1024);
-        }
-    }
-    // Pipeline start: K(0), V(0), K(1) (V(1) follows barrier A of the first iteration).  Every wave runs
-    // all ntq iterations, also over tiles past the end of the split (their loads are clamped, their
-    // keys masked), so that all eight waves meet at every barrier.
-    dma_half_tile<D, PAGED, false>(addr, kring_lds, tile_t0(0), last_tok, lane, team);
-    dma_half_tile<D, PAGED, true>(addr, vring_lds, tile_t0(0), last_tok, lane, team);
-    dma_half_tile<D, PAGED, false>(addr, kring_lds + G::SLOT, tile_t0(1), last_tok, lane, team);
-    wait_loads<3 * (G::NLD / 2)>();                      // everything older than the three half tiles: Q
-    __syncthreads();
 
     bf16x8 qf[RBT][G::KS];
     int lim[RBT];
 #pragma unroll
     for (int rb = 0; rb < RBT; ++rb) {
-        const int row = team * RPT + rb * 16 + ln;
+        const int row = row0 + rb * 16 + ln;
         const bool real = row < R;
         const int qi = real ? row / a.G : 0;
         lim[rb] = min(real ? L - Q + qi : L - 1, c1 - 1);
 #pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
             const int c = (ks * 4 + lg) ^ k_swz<D>(row);
-            u32x4 raw = *reinterpret_cast<const u32x4*>(qlds + row * G::ROWB + c * 16);
+            u32x4 raw = *reinterpret_cast<const u32x4*>(w.qlds + row * G::ROWB + c * 16);
             if (!real) raw = u32x4{0, 0, 0, 0};
             qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
         }
@@ -643,22 +612,22 @@ __global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLa
     // (tiles of this quarter past the end of the split start at t0 >= c1: every key of theirs is masked)
 
     for (int it = 0; it < ntq; ++it) {
-        char* kt = kring + (it & 1) * G::SLOT;
-        char* vt = vring + (it & 1) * G::SLOT;
+        char* kt = w.kring + (it & 1) * G::SLOT;
+        char* vt = w.vring + (it & 1) * G::SLOT;
         const int t0 = tile_t0(it);
         floatx4 s[2][RBT];
         bf16x8 pb[RBT];
 
         wait_loads<kWait>();                         // own half of K(it) has landed
         __syncthreads();                             // barrier A
-        dma_half_tile<D, PAGED, true>(addr, vring_lds + ((it + 1) & 1) * G::SLOT, tile_t0(it + 1), last_tok, lane, team);
+        dma_half_tile<D, PAGED, true>(w.addr, w.vring_lds + ((it + 1) & 1) * G::SLOT, tile_t0(it + 1), last_tok, lane, team);
         score_tile<D, RBT>(s, qf, kt, lane);
         softmax_tile<D, RBT>(st, s, pb, t0, t0 >= first_masked_t0, lim, c, lane);
 
         wait_loads<kWait>();                         // own half of V(it) has landed
         lds_reads_done();
         __syncthreads();                             // barrier B
-        dma_half_tile<D, PAGED, false>(addr, kring_lds + (it & 1) * G::SLOT, tile_t0(it + 2), last_tok, lane, team);
+        dma_half_tile<D, PAGED, false>(w.addr, w.kring_lds + (it & 1) * G::SLOT, tile_t0(it + 2), last_tok, lane, team);
         pv_tile<D, RBT>(st, pb, vt, lane);
         lds_reads_done();
     }
@@ -670,16 +639,14 @@ __global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLa
         st.l[rb] += __shfl_xor(st.l[rb], 32);
     }
 
-    // ---- combine the four waves of each team (fixed order) and write the split's partial
+    // ---- combine the four waves of the team (fixed order)
     __syncthreads();                                  // all rings are dead from here on
     constexpr int OROW = D + 4;
-    float* obuf = reinterpret_cast<float*>(smem) + team * 2 * RPT * OROW;     // this team's [2][RPT][OROW]
-    float* mlbuf = reinterpret_cast<float*>(smem) + 2 * 2 * RPT * OROW;       // [8 waves][RPT][2]
     if (lg == 0) {
 #pragma unroll
         for (int rb = 0; rb < RBT; ++rb) {
-            mlbuf[(wave * RPT + rb * 16 + ln) * 2 + 0] = st.m[rb];
-            mlbuf[(wave * RPT + rb * 16 + ln) * 2 + 1] = st.l[rb];
+            mlbuf[(wave * MLS + rb * 16 + ln) * 2 + 0] = st.m[rb];
+            mlbuf[(wave * MLS + rb * 16 + ln) * 2 + 1] = st.l[rb];
         }
     }
     float* mine = obuf + (pr & 1) * RPT * OROW;
@@ -698,14 +665,14 @@ __global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLa
         float mw[kWaves];
         float mm = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            mw[w] = mlbuf[((team * kWaves + w) * RPT + row) * 2];
-            mm = fmaxf(mm, mw[w]);
+        for (int v = 0; v < kWaves; ++v) {
+            mw[v] = mlbuf[((team * kWaves + v) * MLS + row) * 2];
+            mm = fmaxf(mm, mw[v]);
         }
         const float m_use = (mm == -INFINITY) ? 0.f : mm;
         float ll = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) ll += mlbuf[((team * kWaves + w) * RPT + row) * 2 + 1] * fast_exp2(mw[w] - m_use);
+        for (int v = 0; v < kWaves; ++v) ll += mlbuf[((team * kWaves + v) * MLS + row) * 2 + 1] * fast_exp2(mw[v] - m_use);
         m_all[rb] = mm;
         l_all[rb] = ll;
         if (pr < 2) {
@@ -719,26 +686,101 @@ __global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLa
         }
     }
     __syncthreads();
-    const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.nsplit + split) * RP;
-    floatx4* po = reinterpret_cast<floatx4*>(a.part_o + pbase * D);
-    const float* oall = reinterpret_cast<const float*>(smem);
-    for (int f = tid; f < R * (D / 4); f += 2 * kWaves * 64) {
-        const int row = f / (D / 4), d4 = f % (D / 4);
-        const int tm = row / RPT, lr = row % RPT;
-        const float* ob = oall + tm * 2 * RPT * OROW;
-        const floatx4 x = *reinterpret_cast<const floatx4*>(ob + lr * OROW + d4 * 4);
-        const floatx4 y = *reinterpret_cast<const floatx4*>(ob + (RPT + lr) * OROW + d4 * 4);
-        po[f] = x + y;
-    }
     if (pr == 0 && lg == 0) {
 #pragma unroll
         for (int rb = 0; rb < RBT; ++rb) {
-            const int row = team * RPT + rb * 16 + ln;
+            const int row = row0 + rb * 16 + ln;
             if (row < R) {
                 a.part_ml[(pbase + row) * 2 + 0] = m_all[rb];
                 a.part_ml[(pbase + row) * 2 + 1] = l_all[rb];
             }
         }
+    }
+}
+
+// Team 0 takes RB0 row blocks, team 1 the next RB1 (RB0 >= RB1): five row blocks run as 3 + 2, so that
+// no wave spends a third of its matrix and softmax work on rows that do not exist.
+template <int D, int RB0, int RB1, bool PAGED>
+__global__ void __launch_bounds__(2 * kWaves * 64) verify_attn_split_wide(AttnLaunch a)
+{
+    using G = Geo<D>;
+    constexpr int RPT0 = RB0 * 16, RPT1 = RB1 * 16;
+    constexpr int RP = RPT0 + RPT1;        // rows of the workgroup (= a.RB * 16)
+    constexpr int MLS = RPT0 > RPT1 ? RPT0 : RPT1;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    WideWave w;
+    w.split = blockIdx.y;
+    w.b = blockIdx.z;
+    w.hkv = a.rot ? (int)((blockIdx.x + w.split) % a.Hkv) : (int)blockIdx.x;
+    w.L = min(a.ctx_lens[w.b], a.max_ctx);
+    w.c0 = split_begin(a, w.split, w.hkv);
+    if (w.c0 >= w.L) return;
+    w.c1 = min(split_end(a, w.split, w.hkv), w.L);
+    w.Q = seq_queries(a, w.b);
+    w.R = w.Q * a.G;
+    const int tid = threadIdx.x;
+    w.lane = tid & 63;
+    w.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    w.team = w.wave >> 2;                                // row team
+    w.pr = w.wave & 3;                                   // token quarter
+    const int lane = w.lane, team = w.team, pr = w.pr;
+
+    const int ntile = (w.c1 - w.c0 + kTile - 1) / kTile;
+    w.ntq = (ntile + kWaves - 1) / kWaves;                                      // tiles per quarter (uniform)
+    w.last_tok = min(w.c1, w.c0 + (pr + 1) * w.ntq * kTile) - 1;
+    auto tile_t0 = [&](int it) { return w.c0 + (pr * w.ntq + it) * kTile; };
+    w.addr = make_row_addr<PAGED>(a, w.b, w.hkv);
+    w.kring = smem + pr * G::WAVE_LDS;
+    w.vring = w.kring + 2 * G::SLOT;
+    w.kring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + pr * G::WAVE_LDS;
+    w.vring_lds = w.kring_lds + 2 * G::SLOT;
+
+    // Q block: RP rows, HBM -> LDS once per workgroup, the eight waves sharing the loads; issued
+    // before the first tiles so that it is complete when only tile loads are outstanding.
+    w.qlds = smem + kWaves * G::WAVE_LDS;
+    {
+        const uint32_t q_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + kWaves * G::WAVE_LDS;
+        constexpr int QI = RP / G::RPI;
+        const int last_row = a.Qmax * a.G - 1;
+        for (int e = w.wave; e < QI; e += 2 * kWaves) {
+            const int row = e * G::RPI + lane / G::CPR;
+            const int rr = min(row, last_row);
+            const int qi = rr / a.G, qg = rr % a.G;
+            const int c = (lane % G::CPR) ^ k_swz<D>(row);
+            const uint32_t off = (uint32_t)(((((int64_t)w.b * a.Qmax + qi) * a.Hq + w.hkv * a.G + qg) * D) * 2) + c * 16;
+            dma16_keep(reinterpret_cast<const char*>(a.q), off, q_lds + e * 1024);
+        }
+    }
+    // Pipeline start: K(0), V(0), K(1) (V(1) follows barrier A of the first iteration).  Every wave runs
+    // all ntq iterations, also over tiles past the end of the split (their loads are clamped, their
+    // keys masked), so that all eight waves meet at every barrier.
+    dma_half_tile<D, PAGED, false>(w.addr, w.kring_lds, tile_t0(0), w.last_tok, lane, team);
+    dma_half_tile<D, PAGED, true>(w.addr, w.vring_lds, tile_t0(0), w.last_tok, lane, team);
+    dma_half_tile<D, PAGED, false>(w.addr, w.kring_lds + G::SLOT, tile_t0(1), w.last_tok, lane, team);
+    wait_loads<3 * (G::NLD / 2)>();                      // everything older than the three half tiles: Q
+    __syncthreads();
+
+    constexpr int OROW = D + 4;
+    float* mlbuf = reinterpret_cast<float*>(smem) + 2 * RP * OROW;              // [8 waves][MLS][2]
+    const int64_t pbase = (((int64_t)w.b * a.Hkv + w.hkv) * a.nsplit + w.split) * RP;
+    if (RB0 == RB1 || team == 0)
+        wide_team<D, RB0, MLS, PAGED>(a, w, smem, team * RPT0, reinterpret_cast<float*>(smem) + team * 2 * RPT0 * OROW,
+                                      mlbuf, pbase);
+    else
+        wide_team<D, RB1, MLS, PAGED>(a, w, smem, RPT0, reinterpret_cast<float*>(smem) + 2 * RPT0 * OROW, mlbuf, pbase);
+
+    // ---- the split's partial: per row the sum of the team's two halves
+    floatx4* po = reinterpret_cast<floatx4*>(a.part_o + pbase * D);
+    const float* oall = reinterpret_cast<const float*>(smem);
+    for (int f = tid; f < w.R * (D / 4); f += 2 * kWaves * 64) {
+        const int row = f / (D / 4), d4 = f % (D / 4);
+        const bool t1 = row >= RPT0;
+        const int lr = t1 ? row - RPT0 : row, rpt = t1 ? RPT1 : RPT0;
+        const float* ob = oall + (t1 ? 2 * RPT0 * OROW : 0);
+        const floatx4 x = *reinterpret_cast<const floatx4*>(ob + lr * OROW + d4 * 4);
+        const floatx4 y = *reinterpret_cast<const floatx4*>(ob + (rpt + lr) * OROW + d4 * 4);
+        po[f] = x + y;
     }
 }
 
@@ -836,20 +878,20 @@ hipError_t launch_split(const AttnLaunch& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int D, int RBT, bool PAGED>
+template <int D, int RB0, int RB1, bool PAGED>
 hipError_t launch_split_wide(const AttnLaunch& a, hipStream_t stream)
 {
-    constexpr int lds = attn_wide_lds_bytes<D, RBT>();
-    auto fn = verify_attn_split_wide<D, RBT, PAGED>;
+    constexpr int lds = attn_wide_lds_bytes<D, RB0, RB1>();
+    auto fn = verify_attn_split_wide<D, RB0, RB1, PAGED>;
     dim3 grid(a.Hkv, a.nsplit, a.B), block(2 * kWaves * 64);
     hipLaunchKernelGGL(fn, grid, block, lds, stream, a);
     return hipGetLastError();
 }
-template <int D, int RBT, bool PAGED>
+template <int D, int RB0, int RB1, bool PAGED>
 hipError_t configure_split_wide()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(verify_attn_split_wide<D, RBT, PAGED>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, attn_wide_lds_bytes<D, RBT>());
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(verify_attn_split_wide<D, RB0, RB1, PAGED>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, attn_wide_lds_bytes<D, RB0, RB1>());
 }
 
 // The split kernels use more dynamic LDS than the default limit allows; raise it once
@@ -869,16 +911,18 @@ hipError_t configure_rb()
     if ((e = configure_split<D, 3, PAGED>()) != hipSuccess) return e;
     if ((e = configure_split<D, 4, PAGED>()) != hipSuccess) return e;
     if ((e = configure_split<D, 5, PAGED>()) != hipSuccess) return e;
-    if ((e = configure_split_wide<D, 2, PAGED>()) != hipSuccess) return e;
-    return configure_split_wide<D, 3, PAGED>();
+    if ((e = configure_split_wide<D, 2, 2, PAGED>()) != hipSuccess) return e;
+    if ((e = configure_split_wide<D, 3, 2, PAGED>()) != hipSuccess) return e;
+    return configure_split_wide<D, 3, 3, PAGED>();
 }
 
 template <int D, bool PAGED>
 hipError_t dispatch_rb(const AttnLaunch& a, hipStream_t stream)
 {
-    if (a.wide) {                                    // a.RB = 2 RBT row blocks
-        if (a.RB == 4) return launch_split_wide<D, 2, PAGED>(a, stream);
-        if (a.RB == 6) return launch_split_wide<D, 3, PAGED>(a, stream);
+    if (a.wide) {                                    // a.RB row blocks over two teams
+        if (a.RB == 4) return launch_split_wide<D, 2, 2, PAGED>(a, stream);
+        if (a.RB == 5) return launch_split_wide<D, 3, 2, PAGED>(a, stream);
+        if (a.RB == 6) return launch_split_wide<D, 3, 3, PAGED>(a, stream);
         return hipErrorInvalidValue;
     }
     switch (a.RB) {
