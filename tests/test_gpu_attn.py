@@ -108,6 +108,16 @@ def test_wide_row_counts_layouts_and_ragged_batches():
     check(cfg, chunk_tokens=512, what="wide paged peaked")
     cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=24, n_kv_heads=3, ctx=(3000, 3000), gamma_choices=(10,), name="wide_d64")
     check(cfg, chunk_tokens=1024)
+    # five row blocks (teams of 3 + 2 blocks): paged, ragged with per-sequence gamma, head-major pages, head_dim 64
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=3, ctx=(600, 4000), gamma_choices=(8, 2), paged=True, **base)
+    inp = wl.gen_attn_inputs(cfg, layer=5)
+    check(cfg, inp, chunk_tokens=512, what="3+2 paged ragged")
+    check(cfg, inp, chunk_tokens=512, head_major=True, what="3+2 paged head-major")
+    cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=21, n_kv_heads=3, ctx=(2900, 2900), gamma_choices=(10,), name="wide_d64_77rows")
+    check(cfg, chunk_tokens=1024)
+    cfg = wl.scaled(wl.CONFIGS["tiny"], n_q_heads=21, n_kv_heads=3, batch=2, ctx=(100, 1500), gamma_choices=(10, 9), paged=True,
+                    name="wide_d64_77rows_paged")
+    check(cfg, chunk_tokens=256)
 
 
 def test_head_dim_64_multi_split():
