@@ -110,6 +110,45 @@ def test_split_planning_on_the_named_workloads_needs_no_gpu():
     assert lib.rapid_lm_head_chunk(None, 128256, 97) == 0 and lib.rapid_lm_head_chunk(None, 0, 9) == 0
 
 
+def test_split_planning_invariants_on_random_shapes():
+    """Seeded random shapes: an accepted shape gets whole tiles of 128 tokens per split, a workspace that holds
+    the partials of every (sequence, kv head, split, packed row) and grows with nothing but those counts; a
+    refused shape gets an error code from the chunk query and 0 bytes from the workspace query."""
+    import random
+    lib = binding.load_library()
+    rng = random.Random(20330)
+    seen_ok = seen_bad = 0
+    for _ in range(400):
+        d = rng.choice([64, 128, 128, 128, 96])
+        hkv = rng.choice([1, 2, 3, 4, 8])
+        group = rng.choice([1, 2, 4, 7, 8])
+        q_max = rng.randint(1, 14)
+        batch = rng.choice([1, 1, 2, 8])
+        max_ctx = rng.choice([1, 100, 4096, 33000, 131072, 1 << 20])
+        layout = rng.choice(["token", "head", "paged"])
+        page = rng.choice([16, 64, 24]) if layout == "paged" else 0
+        s = _shape(batch, q_max, hkv * group, hkv, d, max_ctx, token_major=layout != "head", page=page)
+        s.chunk_tokens = rng.choice([0, 0, 0, 1000, 128, 5000])
+        chunk = lib.rapid_verify_attn_chunk(None, ctypes.byref(s))
+        ws = lib.rapid_verify_attn_workspace_bytes(None, ctypes.byref(s))
+        rows = q_max * group
+        legal = d in (64, 128) and rows <= 96 and page in (0, 16, 64) and q_max <= max_ctx
+        if chunk <= 0:
+            seen_bad += 1
+            assert ws == 0 and chunk in (-1, -3), (chunk, ws)
+            assert not legal or max_ctx >= 1 << 20, "a legal shape was refused"   # (2^20 tokens x 2 KiB overflow 32 bits)
+            continue
+        seen_ok += 1
+        assert legal
+        assert chunk % 128 == 0
+        if s.chunk_tokens:
+            assert chunk == -(-s.chunk_tokens // 128) * 128
+        nsplit = -(-max_ctx // chunk)
+        need = batch * hkv * nsplit * (-(-rows // 16) * 16) * (d + 2) * 4
+        assert need <= ws <= need + 2 * 256, (ws, need)
+    assert seen_ok > 100 and seen_bad > 30
+
+
 def test_product_path_has_no_cpu_fallback():
     """Without a GPU the binding refuses to construct instead of computing elsewhere."""
     import torch
