@@ -42,7 +42,23 @@ def _attn_cases(n=36):
     return out
 
 
-@pytest.mark.parametrize("c", _attn_cases(), ids=lambda c: f"attn{c['i']}")
+def _wide_attn_cases(n=16):
+    """The same sweep over shapes with 65..96 packed rows only (the two-team kernel: five and six row blocks)."""
+    rng = np.random.default_rng(2025)
+    out = []
+    pairs = [(gm, gr) for gm in range(0, 14) for gr in range(1, 9) if 65 <= (gm + 1) * gr <= 96]
+    for i in range(n):
+        gmax, group = pairs[int(rng.integers(0, len(pairs)))]
+        lo = int(rng.integers(gmax + 1, 400))
+        paged = bool(rng.integers(0, 2))
+        out.append(dict(i=100 + i, d=int(rng.choice([64, 128])), hkv=int(rng.choice([1, 2, 3, 4])), group=group,
+                        batch=int(rng.choice([1, 2, 3])), ctx=(lo, lo + int(rng.integers(0, 5000))), paged=paged,
+                        page=int(rng.choice([16, 32, 128])), chunk=int(rng.choice([0, 128, 256, 640, 1024, 2048])),
+                        head_major=bool(rng.integers(0, 2)), gammas=tuple(sorted({gmax, int(rng.integers(0, gmax + 1))}))))
+    return out
+
+
+@pytest.mark.parametrize("c", _attn_cases() + _wide_attn_cases(), ids=lambda c: f"attn{c['i']}")
 def test_random_attention_case(c):
     cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], name=f"rand{c['i']}", batch=c["batch"], n_kv_heads=c["hkv"],
                     n_q_heads=c["hkv"] * c["group"], head_dim=c["d"], ctx=c["ctx"], gamma_choices=c["gammas"],
