@@ -68,11 +68,16 @@ int rapid_last_hip_error(const rapid_ctx* ctx);
  *   RAPID_OPT_ACCEPT_SLICE    Vocabulary entries per workgroup of rapid_accept's row pass:
  *       0 = chosen from the batch size (default), or 4096, 8192, 16384.  Results of the accept
  *       tests may differ in the last bits of accept_ratio between slice sizes (fp32 sums).
+ *   RAPID_OPT_PROBE_SKEW      rapid_hbm_read_probe only: of every two consecutive workgroups the
+ *       first reads (32 + value)/32 and the second (32 - value)/32 of the mean share, as
+ *       rapid_verify_attn splits the tokens of a pair of KV splits unevenly when its grid is one
+ *       workgroup per compute unit.  0 <= value <= 16; default 0 (equal shares).
  * Returns RAPID_EINVAL for an unknown option or a value out of range.
  */
 typedef enum rapid_option {
     RAPID_OPT_ACCEPT_WAIT_US = 1,
-    RAPID_OPT_ACCEPT_SLICE = 2
+    RAPID_OPT_ACCEPT_SLICE = 2,
+    RAPID_OPT_PROBE_SKEW = 3
 } rapid_option;
 int rapid_set_option(rapid_ctx* ctx, int option, int64_t value);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "librapid.so")
 RAPID_OK = 0
 RAPID_EINVAL, RAPID_EALIGN, RAPID_EUNSUPPORTED, RAPID_EWORKSPACE, RAPID_EHIP, RAPID_ETOOLARGE = -1, -2, -3, -4, -5, -6
 STATIC_SCRATCH_BYTES = 32 << 20
-OPT_ACCEPT_WAIT_US, OPT_ACCEPT_SLICE = 1, 2
+OPT_ACCEPT_WAIT_US, OPT_ACCEPT_SLICE, OPT_PROBE_SKEW = 1, 2, 3
 EXPORTS = ["rapid_create", "rapid_destroy", "rapid_strerror", "rapid_last_hip_error", "rapid_set_option",
            "rapid_verify_attn_chunk", "rapid_verify_attn_workspace_bytes", "rapid_verify_attn",
            "rapid_verify_attn_static",

@@ -11,13 +11,19 @@ namespace {
 constexpr int kBlock = 16384;      // bytes per ring slot
 constexpr int kWaves = 4;
 
-__global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, int64_t nblock, uint32_t* sink)
+// Workgroups 2i and 2i + 1 share the blocks of pair i; the first takes (32 + skew)/64 of them (skew = 0:
+// equal shares).  Inside a workgroup every wave streams its own contiguous quarter.
+__global__ void __launch_bounds__(kWaves * 64) hbm_read_stream(const char* buf, int64_t nblock, int skew, uint32_t* sink)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t w = (int64_t)blockIdx.x * kWaves + wave, nw = (int64_t)gridDim.x * kWaves;
-    const int64_t b0 = nblock * w / nw, b1 = nblock * (w + 1) / nw;   // this wave's blocks
+    const int64_t npair = (gridDim.x + 1) / 2, pair = blockIdx.x >> 1;
+    const int64_t p0 = nblock * pair / npair, p1 = nblock * (pair + 1) / npair;        // the pair's blocks
+    const bool alone = 2 * pair + 1 >= gridDim.x;                                      // an odd grid's last workgroup
+    const int64_t cut = alone ? p1 : p0 + (p1 - p0) * (32 + skew) / 64;
+    const int64_t g0 = (blockIdx.x & 1) ? cut : p0, g1 = (blockIdx.x & 1) ? p1 : cut;  // this workgroup's blocks
+    const int64_t b0 = g0 + (g1 - g0) * wave / kWaves, b1 = g0 + (g1 - g0) * (wave + 1) / kWaves;
     const int n = (int)(b1 - b0);
     if (n <= 0) return;
     const char* base = buf + b0 * kBlock;
@@ -62,6 +68,6 @@ hipError_t launch_hbm_read_probe(const rapid_ctx* ctx, const void* buf, size_t b
 {
     const int64_t nblock = (int64_t)(bytes / kBlock);
     hipLaunchKernelGGL(hbm_read_stream, dim3(ctx->n_cu), dim3(kWaves * 64), kWaves * 2 * kBlock, stream,
-                       static_cast<const char*>(buf), nblock, sink);
+                       static_cast<const char*>(buf), nblock, ctx->probe_skew, sink);
     return hipGetLastError();
 }

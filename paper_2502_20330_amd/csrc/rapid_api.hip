@@ -169,6 +169,7 @@ int rapid_create(rapid_ctx** out, int device)
     c->static_scratch = scratch_ptr;
     c->accept_wait_ticks = 100 * 100;                 // 100 us
     c->accept_slice = 0;
+    c->probe_skew = 0;
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c->last_hip_error = 0;
     *out = c;
@@ -204,6 +205,10 @@ int rapid_set_option(rapid_ctx* ctx, int option, int64_t value)
         case RAPID_OPT_ACCEPT_SLICE:
             if (value != 0 && value != 4096 && value != 8192 && value != 16384) return RAPID_EINVAL;
             ctx->accept_slice = (int)value;
+            return RAPID_OK;
+        case RAPID_OPT_PROBE_SKEW:
+            if (value < 0 || value > 16) return RAPID_EINVAL;
+            ctx->probe_skew = (int)value;
             return RAPID_OK;
     }
     return RAPID_EINVAL;

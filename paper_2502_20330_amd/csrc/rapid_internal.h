@@ -11,6 +11,7 @@ struct rapid_ctx {
     void* static_scratch;   // device address of this GPU's copy of the library's static scratch array
     int64_t accept_wait_ticks;   // bound of every inter-workgroup wait of the accept pass, 10 ns ticks
     int accept_slice;            // entries per workgroup of the accept row pass (0 = automatic)
+    int probe_skew;              // streaming probe: 32nds of the mean share moved from odd to even workgroups
 };
 
 // ---- verify attention (verify_attn.hip)

@@ -355,6 +355,29 @@ def test_hbm_read_probe_runs_and_checks_arguments():
     import ctypes
     bad = r.lib.rapid_hbm_read_probe(r._ctx, ctypes.c_void_p(buf.data_ptr()), 1000, None, None)
     assert bad == binding.RAPID_EINVAL
+    # Every 16 KiB block is looked at by some wave, also with uneven shares per workgroup pair: the kernel
+    # writes `sink` when the XOR of the words a lane inspects (word `lane` of each block) is one constant,
+    # so a buffer of zeros with that constant planted in one block must set it.
+    magic = 0x9E3779B9
+    for skew in (0, 3, 16):
+        r.set_option(binding.OPT_PROBE_SKEW, skew)
+        for nblock in (150, 5000):
+            z = torch.zeros(nblock * 16384 // 4, dtype=torch.int32, device="cuda")
+            sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+            rng = np.random.default_rng(nblock + skew)
+            picks = [0, nblock - 1] + [int(x) for x in rng.integers(0, nblock, 24)]
+            for blk in picks:
+                lane = int(rng.integers(0, 64))
+                z[blk * 4096 + lane] = magic - (1 << 32)
+                sink.zero_()
+                rc = r.lib.rapid_hbm_read_probe(r._ctx, ctypes.c_void_p(z.data_ptr()), nblock * 16384,
+                                                ctypes.c_void_p(sink.data_ptr()), None)
+                assert rc == 0
+                torch.cuda.synchronize()
+                assert int(sink.item()) & 0xFFFFFFFF == magic, (skew, nblock, blk, lane)
+                z[blk * 4096 + lane] = 0
+    r.set_option(binding.OPT_PROBE_SKEW, 0)
+    assert r.lib.rapid_set_option(r._ctx, binding.OPT_PROBE_SKEW, 17) == binding.RAPID_EINVAL
 
 
 @pytest.mark.parametrize("name", ["drafter_decode_8k", "drafter_decode_16k_b8"])
