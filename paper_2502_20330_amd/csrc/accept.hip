@@ -561,7 +561,40 @@ __global__ void __launch_bounds__(kThreads, 4) accept_rows(AcceptLaunch a, Ws ws
         if (pair) {
             gather(own_t, own_d);
             STAMP_AT(id, 3);
-            if (tid < 64) {
+            if (ext_t || ext_d) {
+                // The caller's statistics are hundreds of pairs per row in memory: all eight waves fetch them at
+                // once (one round trip) and two block reductions combine them (a side without supplied statistics
+                // brings its W gathered pairs the same way); every workgroup of the row pair gets the same bits.
+                float2 vt[2], vd[2];                          // pairs tid and tid + kThreads; beyond: the loops below
+                float mt = -INFINITY, md = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int i = tid + j * kThreads;
+                    vt[j] = i < n_t ? pair_t(i) : make_float2(-INFINITY, 0.f);
+                    vd[j] = i < n_d ? pair_d(i) : make_float2(-INFINITY, 0.f);
+                    mt = fmaxf(mt, vt[j].x);
+                    md = fmaxf(md, vd[j].x);
+                }
+                for (int i = tid + 2 * kThreads; i < n_t; i += kThreads) mt = fmaxf(mt, pair_t(i).x);
+                for (int i = tid + 2 * kThreads; i < n_d; i += kThreads) md = fmaxf(md, pair_d(i).x);
+                block_reduce2(mt, md, lds.red, bank, OpMaxF(), OpMaxF());
+                float st = 0.f, sd = 0.f;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (vt[j].y > 0.f) st += vt[j].y * fexp2((vt[j].x - mt) * c);
+                    if (vd[j].y > 0.f) sd += vd[j].y * fexp2((vd[j].x - md) * c);
+                }
+                for (int i = tid + 2 * kThreads; i < n_t; i += kThreads) {
+                    const float2 v = pair_t(i);
+                    if (v.y > 0.f) st += v.y * fexp2((v.x - mt) * c);
+                }
+                for (int i = tid + 2 * kThreads; i < n_d; i += kThreads) {
+                    const float2 v = pair_d(i);
+                    if (v.y > 0.f) sd += v.y * fexp2((v.x - md) * c);
+                }
+                block_reduce2(st, sd, lds.red, bank, OpAddF(), OpAddF());
+                if (tid == 0) lds.norm = PairNorm{mt, __log2f(st), md, __log2f(sd)};
+            } else if (tid < 64) {
                 PairNorm r;
                 wave_combine_f32(pair_t, n_t, c, r.Mt, r.l2St);
                 wave_combine_f32(pair_d, n_d, c, r.Md, r.l2Sd);
