@@ -199,5 +199,38 @@ def test_batched_head_feeds_the_batched_accept():
     assert res["max_ratio_rel_err"] < 1e-4, res
 
 
+@pytest.mark.parametrize("V,chunk", [(20000, 16), (20000, 48), (5000, 16), (128256, 512), (4097, 4097)])
+@pytest.mark.parametrize("sides", ["both", "target", "draft"])
+def test_accept_with_statistics_over_any_partition(V, chunk, sides):
+    """rapid_accept_prestats takes the (max, sum exp) pairs of any partition of the vocabulary: here partitions
+    of 1 to 1250 chunks per row (more chunks than a workgroup has threads included), written by the oracle's
+    chunk statistics from the logits, for both rows, the target rows only and the draft rows only; a batch with
+    different draft counts; against the oracle's accept on the same logits."""
+    B, g, T = 3, 5, 0.7
+    rng = np.random.default_rng(V + chunk)
+    zt = (rng.standard_normal((B, g + 1, V)) * 3).astype(np.float32)
+    zd = (zt[:, :g] + rng.standard_normal((B, g, V))).astype(np.float32)
+    tok = np.argmax(zd.astype(np.float64) / T + rng.gumbel(size=zd.shape), -1).astype(np.int32)
+    u = rng.random((B, g + 1)).astype(np.float32)
+    gammas = np.array([5, 2, 0], dtype=np.int32)
+
+    def stats(z):
+        cmax, csum = oracle.chunk_stats(z.reshape(-1, V).astype(np.float64), chunk, T)
+        return st_dev(np.stack([cmax, csum], -1))
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    kw = {}
+    if sides in ("both", "target"):
+        kw["target_stats"] = stats(zt)
+    if sides in ("both", "draft"):
+        kw["draft_stats"] = stats(zd)
+    got = gu.rapid().rapid_accept(dev(zt), dev(zd), dev(tok), 2.0, dev(u), gammas=dev(gammas), temperature=T, **kw)
+    torch.cuda.synchronize()
+    ref = oracle.accept(zt, zd, tok, u, eta=2.0, temperature=T, gammas=gammas)
+    res = gu.compare_accept(tuple(x.cpu().numpy() for x in got), ref, gammas, g)
+    assert res["n_mismatch"] == 0 and res["token_mismatch"] == 0 and res["exempt_sequences"] == 0, res
+    assert res["max_ratio_rel_err"] < 1e-4, res
+
+
 def st_dev(st):
     return torch.from_numpy(st.astype(np.float32)).cuda().contiguous()
