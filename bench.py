@@ -39,9 +39,10 @@ def parse_args():
     ap.add_argument("--chunk-tokens", type=int, default=0, help="KV split size override (0 = library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers of attention the oracle is timed on")
-    ap.add_argument("--kv-layout", choices=["head-major", "token-major"], default="head-major",
+    ap.add_argument("--kv-layout", choices=["head-major", "token-major", "head-major-kv-interleaved"], default="head-major",
                     help="KV cache memory order: [B,Hkv,L,d] (default, the layout the library prefers) or "
-                         "[B,L,Hkv,d]; paged: [pages,Hkv,page,d] or [pages,page,Hkv,d]")
+                         "[B,L,Hkv,d]; paged: [pages,Hkv,page,d] or [pages,page,Hkv,d]; head-major-kv-interleaved: K and V "
+                         "in one tensor [B,Hkv,L,2,d] / [pages,Hkv,page,2,d], the two rows of a (token, head) adjacent")
     ap.add_argument("--with-lm-head", action="store_true",
                     help="also run the target's output head (hidden x vocab bf16 weights) inside every step and feed "
                          "its logits and row statistics to the accept pass (batch 1 workloads)")
@@ -109,11 +110,9 @@ def also_workload(r, cfg, n_layers, head_major, steps=5, warmup=2):
     for layer in range(nbuf):
         g = torch.Generator(device=dev)
         g.manual_seed(1000 * wl.SEED_QKV + layer)
-        k = kv_randn(g)
-        if cfg.k_scale != 1.0:
-            k.mul_(cfg.k_scale)
+        k, v = kv_pair(g)
         ks.append(k)
-        vs.append(kv_randn(g))
+        vs.append(v)
         qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
     out = torch.empty_like(qs[0])
     g = torch.Generator(device=dev)
@@ -263,13 +262,27 @@ def main():
     page_table = torch.from_numpy(seqs.page_table).to(dev) if cfg.paged else None
     # logical shape is always [B or pages, tokens, Hkv, d]; the memory order is the layout's
     kv_shape = (seqs.n_pages, cfg.page_size, Hkv, d) if cfg.paged else (B, seqs.max_ctx, Hkv, d)
-    head_major = args.kv_layout == "head-major"
+    head_major = args.kv_layout != "token-major"
+    interleaved = args.kv_layout == "head-major-kv-interleaved"   # K and V rows of a (token, head) adjacent, one tensor
 
     def kv_randn(g):
         if head_major:
             t = torch.randn((kv_shape[0], Hkv, kv_shape[1], d), dtype=torch.bfloat16, device=dev, generator=g)
             return t.permute(0, 2, 1, 3)
         return torch.randn(kv_shape, dtype=torch.bfloat16, device=dev, generator=g)
+
+    def kv_pair(g):
+        """(k, v) of one layer, logical shape kv_shape each."""
+        if interleaved:
+            t = torch.randn((kv_shape[0], Hkv, kv_shape[1], 2, d), dtype=torch.bfloat16, device=dev, generator=g)
+            if cfg.k_scale != 1.0:
+                t[:, :, :, 0, :].mul_(cfg.k_scale)
+            t = t.permute(0, 2, 1, 3, 4)
+            return t[:, :, :, 0, :], t[:, :, :, 1, :]
+        k = kv_randn(g)
+        if cfg.k_scale != 1.0:
+            k.mul_(cfg.k_scale)
+        return k, kv_randn(g)
 
     # Distinct cache buffers: at least one per layer, and enough of them (>= 1 GiB together) that no
     # launch finds its cache in the 256 MB Infinity Cache left there by an earlier one.
@@ -281,11 +294,9 @@ def main():
     for layer in range(nbuf):
         g = torch.Generator(device=dev)
         g.manual_seed(1000 * wl.SEED_QKV + layer)
-        k = kv_randn(g)
-        if cfg.k_scale != 1.0:
-            k.mul_(cfg.k_scale)
+        k, v = kv_pair(g)
         ks.append(k)
-        vs.append(kv_randn(g))
+        vs.append(v)
         qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
     outs = [torch.empty_like(qs[0]) for _ in range(2)]
     g = torch.Generator(device=dev)
@@ -439,7 +450,8 @@ def main():
     acc_gbps = logit_bytes / (acc_ms * 1e-3) / 1e9
 
     # the committed counter summary covers the default launch configuration only
-    profiled = (cfg.name == "llama8b_128k_step" and head_major and not args.chunk_tokens and layers == cfg.layers)
+    profiled = (cfg.name == "llama8b_128k_step" and head_major and not interleaved and not args.chunk_tokens
+                and layers == cfg.layers)
     result = {
         "metric": "verify-step \u00b5s + effective KV GB/s (% HBM peak) at 128K ctx, gamma=8",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -448,8 +460,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "ctx_tokens": tokens, "gamma": gmax, "vocab": V, "eta": cfg.eta,
-                   "kv_layout": (("[pages,Hkv,16,d]" if head_major else "[pages,16,Hkv,d]") if cfg.paged
-                                 else ("[B,Hkv,L,d]" if head_major else "[B,L,Hkv,d]")), "chunk_tokens": chunk,
+                   "kv_layout": (("[pages,Hkv,16,2,d] (K and V rows adjacent)" if interleaved
+                                  else "[pages,Hkv,16,d]" if head_major else "[pages,16,Hkv,d]") if cfg.paged
+                                 else ("[B,Hkv,L,2,d] (K and V rows adjacent)" if interleaved
+                                       else "[B,Hkv,L,d]" if head_major else "[B,L,Hkv,d]")), "chunk_tokens": chunk,
                    "kv_bytes_per_step": kv_bytes_step},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBPS, 4),
         "breakdown_us": {"attention_all_layers": round(attn_ms * 1e3, 1),

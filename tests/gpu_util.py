@@ -35,13 +35,21 @@ def bf16_to_host(t: torch.Tensor) -> np.ndarray:
     return wl.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
 
 
-def run_attn_case(cfg, inp, *, chunk_tokens=0, scale=None, want_lse=True, head_major=False):
+def run_attn_case(cfg, inp, *, chunk_tokens=0, scale=None, want_lse=True, head_major=False, kv_interleaved=False):
     """Runs GPU and oracle on one AttnInputs; returns (gpu_out f64, ref f64, gpu_lse, ref_lse).
-    head_major: the GPU sees the same cache re-stored in [B, Hkv, L, d] memory order."""
+    head_major: the GPU sees the same cache re-stored in [B, Hkv, L, d] memory order.
+    kv_interleaved: K and V in ONE allocation [B, Hkv, L, 2, d] (or [B, L, Hkv, 2, d]): the K row and the V row
+    of a (token, head) are adjacent, v = k + d elements, and both are addressed with the same strides."""
     s = inp.seqs
     scale = cfg.softmax_scale if scale is None else scale
     q, k, v = bf16_to_dev(inp.q), bf16_to_dev(inp.k), bf16_to_dev(inp.v)
-    if head_major:
+    if kv_interleaved:
+        kv = torch.stack([k, v], dim=3)                                     # [B or pages, tokens, Hkv, 2, d]
+        if head_major:
+            kv = kv.permute(0, 2, 1, 3, 4).contiguous().permute(0, 2, 1, 3, 4)
+        k, v = kv[:, :, :, 0, :], kv[:, :, :, 1, :]
+        assert k.stride() == v.stride() and v.data_ptr() - k.data_ptr() == 2 * cfg.head_dim
+    elif head_major:
         k = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
         v = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
     ctx = torch.from_numpy(s.ctx_lens).cuda()

@@ -157,6 +157,20 @@ def test_head_major_cache_strides():
     assert torch.equal(base, alt)
 
 
+@pytest.mark.parametrize("head_major", [False, True])
+def test_k_and_v_rows_interleaved_in_one_allocation(head_major):
+    """K and V of a (token, head) next to each other in one tensor, [B, Hkv, L, 2, d] or [B, L, Hkv, 2, d]: the
+    same entry point through its strides (v = k + d elements).  Contiguous and paged, narrow and wide row
+    counts, several splits; against the oracle."""
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=2, ctx=(900, 5000), n_q_heads=8, n_kv_heads=2, name="kv_interleaved")
+    check(cfg, chunk_tokens=1024, head_major=head_major, kv_interleaved=True)
+    cfg = wl.scaled(wl.CONFIGS["llama8b_32k"], batch=2, ctx=(300, 3000), n_q_heads=16, n_kv_heads=2, gamma_choices=(8, 3),
+                    paged=True, name="kv_interleaved_paged_wide")
+    check(cfg, chunk_tokens=512, head_major=head_major, kv_interleaved=True)
+    cfg = wl.scaled(wl.CONFIGS["tiny"], ctx=(2000, 2000), n_q_heads=8, n_kv_heads=4, name="kv_interleaved_d64")
+    check(cfg, chunk_tokens=0, head_major=head_major, kv_interleaved=True)
+
+
 @pytest.mark.parametrize("L", [1919, 1920, 1921, 2048, 2175, 2176, 2177, 4095, 4097, 6015, 6016, 6017, 6271, 6273, 8192])
 def test_head_major_uneven_split_pairs(L):
     """[B, Hkv, L, d] cache with one workgroup per compute unit or fewer: the library then
