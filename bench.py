@@ -110,9 +110,11 @@ def also_workload(r, cfg, n_layers, head_major, steps=5, warmup=2):
     for layer in range(nbuf):
         g = torch.Generator(device=dev)
         g.manual_seed(1000 * wl.SEED_QKV + layer)
-        k, v = kv_pair(g)
+        k = kv_randn(g)
+        if cfg.k_scale != 1.0:
+            k.mul_(cfg.k_scale)
         ks.append(k)
-        vs.append(v)
+        vs.append(kv_randn(g))
         qs.append(torch.randn((B, Q, Hq, d), dtype=torch.bfloat16, device=dev, generator=g))
     out = torch.empty_like(qs[0])
     g = torch.Generator(device=dev)
